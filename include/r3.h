@@ -1,0 +1,248 @@
+/*
+ * r3.h -- C ABI of the replay-evaluation library (libr3.so), gfx950 / HIP.
+ *
+ * The library implements the device-side inner loop of replay-based kernel
+ * evaluation as the paper's Section V describes it: a recorded pre-execution
+ * device state (prologue snapshot) is restored, a candidate kernel runs on it,
+ * and the resulting state is checked against the recorded post-execution state
+ * (epilogue snapshot), bitwise by default or under per-variable tolerances
+ * (Section V-B "Replay, Transformation, and Auto-Tuning", Section V-C
+ * "Correctness Checking").  Snapshots stay resident on the device and all
+ * verdicts are reduced on the device, which is the design rule of the
+ * persistent replay server (Section V-D).
+ *
+ * Conventions that hold for every entry point
+ *   - Return value: R3_OK (0) or a negative r3_status.  Nothing throws or
+ *     aborts across this boundary.  r3_last_error() gives a message for the
+ *     last failure on a context.
+ *   - "host" pointers are ordinary process memory; "device" pointers are HIP
+ *     device allocations on the context's GPU.  The library never allocates or
+ *     frees device memory: snapshots, live arena, result arrays and the table
+ *     workspace are owned by the caller for as long as the objects that refer
+ *     to them are in use.
+ *   - Device base pointers of arenas must be 16-byte aligned.
+ *   - All GPU work is enqueued on the caller's stream (a hipStream_t passed as
+ *     void*, NULL = the default stream).  Calls return without waiting unless
+ *     stated otherwise.
+ *   - One r3_ctx, and one r3_table, may be used by one host thread and one
+ *     stream at a time: a table's workspace holds the partial results of the
+ *     call in flight.
+ *   - Arguments that the host can check (NULL pointers, table contents,
+ *     workspace size) are rejected before any GPU work is enqueued.
+ *
+ * Memory model ("arena"): a recorded device state is a flat byte range
+ * [0, arena_bytes).  The prologue snapshot, the epilogue snapshot and the live
+ * memory the candidate runs on share this layout, so one offset addresses the
+ * same variable in all of them.  A region table names the spans of the arena
+ * that an operation touches.
+ */
+#ifndef R3_H
+#define R3_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  R3_OK = 0,
+  R3_EINVAL = -1,     /* NULL pointer, n == 0, unknown dtype/mode/policy, bad tolerance   */
+  R3_EALIGN = -2,     /* offset/bytes not a multiple of the element size; base not 16 B   */
+  R3_ERANGE = -3,     /* region reaches past arena_bytes                                   */
+  R3_EOVERLAP = -4,   /* two non-empty regions share a byte                                */
+  R3_ENOSPC = -5,     /* workspace too small / too many replays for the workspace          */
+  R3_EHIP = -6,       /* a HIP runtime call failed                                         */
+  R3_ECANDIDATE = -7  /* the candidate's launch callback or its kernel launch failed       */
+} r3_status;
+
+/* Element types of a region: 1, 4, 8, 4, 2 bytes. */
+typedef enum { R3_U8 = 0, R3_F32 = 1, R3_F64 = 2, R3_I32 = 3, R3_BF16 = 4 } r3_dtype;
+
+/* Section V-C: bitwise equality is the default criterion; tolerances apply only
+ * to regions the user marks (the role of the paper's `annotate`). */
+typedef enum { R3_CMP_BITWISE = 0, R3_CMP_TOL = 1 } r3_cmp_mode;
+
+/* When r3_eval_candidate validates: after every replay, only the first, only the last. */
+typedef enum { R3_POLICY_EVERY = 0, R3_POLICY_FIRST = 1, R3_POLICY_LAST = 2 } r3_compare_policy;
+
+#define R3_NO_INDEX UINT64_MAX   /* first_mismatch / first_index when nothing mismatched */
+#define R3_NO_REGION UINT32_MAX  /* first_region when nothing mismatched                 */
+#define R3_MAX_REPLAYS 1024u     /* warmup + reps accepted by r3_eval_candidate          */
+
+/* One span of the arena (40 bytes, host memory, caller-owned).
+ * offset and bytes are multiples of the element size; bytes may be 0.
+ * rtol and atol are finite and >= 0 (checked in both modes, used in R3_CMP_TOL). */
+typedef struct {
+  uint64_t offset;
+  uint64_t bytes;
+  uint32_t dtype; /* r3_dtype    */
+  uint32_t mode;  /* r3_cmp_mode */
+  double rtol;
+  double atol;
+} r3_region;
+
+/* Verdict for one region (40 bytes, device memory, written by r3_compare).
+ * Element i of the region is "c" in live memory and "g" in the golden snapshot.
+ *   - equal bit patterns: match, error 0 (also equal NaNs and infinities);
+ *   - different bits and, for F32/F64/BF16, c or g NaN or infinite: mismatch,
+ *     both errors +Inf;
+ *   - else, in binary64 with one rounding per operation and no fused
+ *     multiply-add:  d = |C - G|,  r = (G == 0) ? 0 : d / |G|;
+ *     BITWISE: mismatch;   TOL: mismatch iff d > atol + rtol*|G|.
+ * max_abs_err / max_rel_err are the maxima of d / r over ALL elements.
+ * first_mismatch is the smallest mismatching element index (region-relative),
+ * R3_NO_INDEX if none.  checksum is the region checksum of the LIVE bytes. */
+typedef struct {
+  uint64_t mismatch_count;
+  uint64_t first_mismatch;
+  double max_abs_err;
+  double max_rel_err;
+  uint64_t checksum;
+} r3_region_result;
+
+/* Verdict over a whole table (40 bytes, device memory, written by r3_compare). */
+typedef struct {
+  uint64_t total_mismatch; /* sum of mismatch_count                               */
+  uint64_t first_index;    /* first_mismatch of region first_region, R3_NO_INDEX  */
+  uint32_t first_region;   /* first region in table order with a mismatch         */
+  uint32_t pass;           /* total_mismatch == 0                                 */
+  double max_abs_err;      /* max over regions                                    */
+  double max_rel_err;
+} r3_summary;
+
+/* What one candidate evaluation returns to the host (56 bytes, host memory).
+ * Section V-B: a replay experiment returns the measured runtime if correct. */
+typedef struct {
+  uint64_t total_mismatch; /* max over the validated replays                       */
+  uint64_t first_index;    /* of the last validated replay                         */
+  uint32_t first_region;
+  uint32_t pass;           /* every validated replay clean and the candidate ran   */
+  double max_abs_err;      /* of the last validated replay                         */
+  double max_rel_err;
+  float ms_min;            /* candidate time over the timed replays (HIP events)   */
+  float ms_median;
+  float ms_max;
+  int32_t candidate_status; /* value the launch callback returned, 0 = launched     */
+} r3_eval_result;
+
+/* The candidate: enqueue the kernel(s) under test on `stream`, operating in
+ * place on the arena at d_live.  Must not synchronise.  Non-zero = failure. */
+typedef int (*r3_launch_fn)(void* user, void* d_live, void* stream);
+
+typedef struct r3_ctx r3_ctx;
+typedef struct r3_table r3_table;
+
+/* ---- library / context ------------------------------------------------- */
+
+/* ABI version, bumped when a struct or signature changes. */
+uint32_t r3_version(void);
+
+/* Static text for a status code; never NULL. */
+const char* r3_strerror(int status);
+
+/* Create a context bound to GPU `device`.  Holds only host-side state (events,
+ * a small pinned staging buffer).  R3_EHIP if the device cannot be used. */
+int r3_ctx_create(r3_ctx** out, int device);
+int r3_ctx_destroy(r3_ctx* ctx);
+
+/* Message of the last failing call on ctx ("" if none); valid until the next call. */
+const char* r3_last_error(const r3_ctx* ctx);
+
+/* ---- region tables ----------------------------------------------------- */
+
+/* Host-only check of a table, usable without a GPU.  Regions are examined in
+ * table order and the first violation decides: per region R3_EINVAL (dtype,
+ * mode, tolerance), then R3_EALIGN, then R3_ERANGE; once every region passes,
+ * R3_EOVERLAP.  host_tbl == NULL or n == 0: R3_EINVAL. */
+int r3_table_validate(const r3_region* host_tbl, uint32_t n, uint64_t arena_bytes);
+
+/* Bytes of device workspace r3_table_create needs for n regions in an arena of
+ * arena_bytes (an upper bound that depends on nothing else). */
+size_t r3_table_workspace_bytes(uint32_t n, uint64_t arena_bytes);
+
+/* Validate host_tbl, split its regions into tiles, and upload regions and tile
+ * list into the caller's workspace d_ws (device, 256-byte aligned, at least
+ * r3_table_workspace_bytes).  Synchronous (uses blocking copies).  The table
+ * refers to d_ws until r3_table_destroy.  host_tbl is not retained. */
+int r3_table_create(r3_ctx* ctx, const r3_region* host_tbl, uint32_t n, uint64_t arena_bytes,
+                    void* d_ws, size_t ws_bytes, r3_table** out);
+int r3_table_destroy(r3_table* tbl);
+
+/* Host-side facts about a table; any out pointer may be NULL. */
+int r3_table_info(const r3_table* tbl, uint32_t* n_regions, uint64_t* n_tiles,
+                  uint32_t* tile_bytes, uint64_t* total_bytes, uint64_t* arena_bytes);
+
+/* ---- the hot path ------------------------------------------------------ */
+
+/* Batched restore (Section V-B "restores the recorded execution context";
+ * Section V-D resident prologue buffers):
+ *   for every region r:  d_live[offset_r .. +bytes_r) = d_snapshot[offset_r .. +bytes_r)
+ * One launch for the whole table.  Bytes outside the regions are not written.
+ * d_snapshot and d_live must not overlap. */
+int r3_restore(r3_ctx* ctx, const r3_table* tbl, const void* d_snapshot, void* d_live,
+               void* stream);
+
+/* Per-region order-independent 64-bit checksum of d_arena's bytes, the cheap
+ * form of the default bitwise criterion of Section V-C (equal checksums of
+ * live and recorded state).  With n = bytes of the region, w_j the j-th
+ * little-endian 64-bit word of the region (bytes past n read as 0),
+ * PHI = 0x9E3779B97F4A7C15, LEN = 0xBB67AE8584CAA73B, all mod 2^64:
+ *   k_j = (j+1)*PHI
+ *   sum = SUM_j ((lo32(w_j)+lo32(k_j)) mod 2^32) * ((hi32(w_j)+hi32(k_j)) mod 2^32) + n*LEN
+ * d_out: device, n_regions values. */
+int r3_checksum(r3_ctx* ctx, const r3_table* tbl, const void* d_arena, uint64_t* d_out,
+                void* stream);
+
+/* Fused validation (Section V-C): one pass over live and golden memory gives,
+ * per region, mismatch count, first mismatching index, max abs / rel error and
+ * the checksum of the live bytes (see r3_region_result), plus the table verdict.
+ * d_out: device, n_regions results.  d_summary: device, one r3_summary, or NULL. */
+int r3_compare(r3_ctx* ctx, const r3_table* tbl, const void* d_live, const void* d_golden,
+               r3_region_result* d_out, r3_summary* d_summary, void* stream);
+
+/* Page-level write-set between two states of `bytes` bytes (Section V-A: the
+ * recorder stores pre- and post-execution state; the pages that differ are what
+ * the kernel wrote).  Bit (p % 64) of d_bitmap[p / 64] is 1 iff page p differs
+ * in any of its valid bytes; unused high bits of the last word are 0.
+ * page_bytes: a power of two, 256 .. 1 MiB.  d_bitmap: device,
+ * ceil(ceil(bytes/page_bytes)/64) words, fully overwritten.  d_dirty_count:
+ * device, one value (number of set bits), or NULL.  bytes == 0 is legal. */
+int r3_dirty_diff(r3_ctx* ctx, const void* d_pre, const void* d_post, uint64_t bytes,
+                  uint32_t page_bytes, uint64_t* d_bitmap, uint64_t* d_dirty_count,
+                  void* stream);
+
+/* Record one replay unit's memory state (Section V-A items "pre-execution
+ * device state" and "post-execution device state"):
+ *   d_prologue[0..arena) = d_live;  launch(user, d_live, stream);
+ *   d_epilogue[0..arena) = d_live;  bitmap = dirty_diff(prologue, epilogue);
+ *   d_pro_cs / d_epi_cs  = per-region checksums of the two snapshots.
+ * The whole arena is copied, not only the table's regions, so the write-set is
+ * defined on every page.  Any of d_bitmap, d_dirty_count, d_pro_cs, d_epi_cs
+ * may be NULL to skip that product.  Waits for the stream before returning.
+ * R3_ECANDIDATE if launch fails. */
+int r3_record(r3_ctx* ctx, const r3_table* tbl, void* d_live, r3_launch_fn launch, void* user,
+              void* d_prologue, void* d_epilogue, uint32_t page_bytes, uint64_t* d_bitmap,
+              uint64_t* d_dirty_count, uint64_t* d_pro_cs, uint64_t* d_epi_cs, void* stream);
+
+/* Evaluate one candidate (Sections V-B, V-C: restore the prologue, execute the
+ * candidate, compare with the epilogue, return the runtime if correct):
+ *   for each of warmup + reps replays:
+ *     r3_restore(restore_tbl, d_prologue -> d_live); time{ launch(user, d_live, stream) };
+ *     r3_compare(check_tbl, d_live, d_epilogue) when compare_policy selects this replay
+ * d_regions (device, check_tbl's n results) holds the last validated replay.
+ * host_out (host) is filled after one wait on the stream at the end.
+ * launch == NULL evaluates the restored state itself (a pure restore+validate
+ * replay).  warmup + reps must be 1 .. R3_MAX_REPLAYS and reps >= 1.
+ * A failing launch stops the loop: R3_ECANDIDATE, host_out->pass = 0. */
+int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
+                      const r3_table* check_tbl, const void* d_epilogue, void* d_live,
+                      r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
+                      uint32_t compare_policy, r3_region_result* d_regions,
+                      r3_eval_result* host_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* R3_H */
