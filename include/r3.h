@@ -162,6 +162,15 @@ int r3_table_validate(const r3_region* host_tbl, uint32_t n, uint64_t arena_byte
  * arena_bytes (an upper bound that depends on nothing else). */
 size_t r3_table_workspace_bytes(uint32_t n, uint64_t arena_bytes);
 
+/* The same for one concrete table: exact rather than an upper bound (0 if the table is
+ * not valid). */
+size_t r3_table_workspace_bytes_exact(const r3_region* host_tbl, uint32_t n, uint64_t arena_bytes);
+
+/* Tuning hook (process-wide, affects tables created afterwards and the two size queries
+ * above): smallest tile a wavefront works on, a power of two 1 KiB .. 16 MiB, and the most
+ * tiles one region is split into, a power of two 64 .. 65536.  0 = default (4 KiB, 8192). */
+int r3_tune_tiles(uint32_t min_tile_bytes, uint32_t max_tiles_per_region);
+
 /* Validate host_tbl, split its regions into tiles, and upload regions and tile
  * list into the caller's workspace d_ws (device, 256-byte aligned, at least
  * r3_table_workspace_bytes).  Synchronous (uses blocking copies).  The table

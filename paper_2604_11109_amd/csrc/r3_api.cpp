@@ -1,0 +1,350 @@
+// Entry points of libr3.so: argument checks, table upload, and the replay / record loops
+// that string the kernels together on the caller's stream.
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "r3_internal.h"
+
+namespace {
+
+int fail(r3_ctx* ctx, int status, const char* what) {
+  if (ctx) ctx->err = what;
+  return status;
+}
+
+int fail_hip(r3_ctx* ctx, hipError_t e, const char* where) {
+  if (ctx) {
+    ctx->err = std::string(where) + ": " + hipGetErrorString(e);
+  }
+  return R3_EHIP;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+// Bind the calling thread to the context's device for the duration of one entry point.
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = true;
+  explicit DeviceGuard(int device) {
+    if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+    if (prev != device) ok = hipSetDevice(device) == hipSuccess;
+  }
+  ~DeviceGuard() {
+    if (prev >= 0) (void)hipSetDevice(prev);
+  }
+};
+
+int check_common(r3_ctx* ctx, const r3_table* tbl) {
+  if (ctx == nullptr) return R3_EINVAL;
+  ctx->err.clear();
+  if (tbl == nullptr) return fail(ctx, R3_EINVAL, "table is NULL");
+  if (tbl->ctx != ctx) return fail(ctx, R3_EINVAL, "table belongs to another context");
+  return R3_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+uint32_t r3_version(void) { return 1; }
+
+const char* r3_strerror(int status) {
+  switch (status) {
+    case R3_OK: return "ok";
+    case R3_EINVAL: return "invalid argument";
+    case R3_EALIGN: return "misaligned offset, size or pointer";
+    case R3_ERANGE: return "region outside the arena";
+    case R3_EOVERLAP: return "regions overlap";
+    case R3_ENOSPC: return "workspace too small";
+    case R3_EHIP: return "HIP runtime error";
+    case R3_ECANDIDATE: return "candidate failed to launch";
+    default: return "unknown status";
+  }
+}
+
+int r3_ctx_create(r3_ctx** out, int device) {
+  if (out == nullptr) return R3_EINVAL;
+  *out = nullptr;
+  int count = 0;
+  if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return R3_EHIP;
+  r3_ctx* ctx = new (std::nothrow) r3_ctx();
+  if (ctx == nullptr) return R3_ENOSPC;
+  ctx->device = device;
+  DeviceGuard guard(device);
+  if (!guard.ok ||
+      hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned), R3_MAX_REPLAYS * sizeof(r3_summary),
+                    hipHostMallocDefault) != hipSuccess) {
+    delete ctx;
+    return R3_EHIP;
+  }
+  *out = ctx;
+  return R3_OK;
+}
+
+int r3_ctx_destroy(r3_ctx* ctx) {
+  if (ctx == nullptr) return R3_EINVAL;
+  DeviceGuard guard(ctx->device);
+  for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
+  if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+  delete ctx;
+  return R3_OK;
+}
+
+const char* r3_last_error(const r3_ctx* ctx) { return ctx ? ctx->err.c_str() : "context is NULL"; }
+
+int r3_table_create(r3_ctx* ctx, const r3_region* host_tbl, uint32_t n, uint64_t arena_bytes,
+                    void* d_ws, size_t ws_bytes, r3_table** out) {
+  if (ctx == nullptr || out == nullptr) return R3_EINVAL;
+  ctx->err.clear();
+  *out = nullptr;
+  int rc = r3::validate_table(host_tbl, n, arena_bytes);
+  if (rc != R3_OK) return fail(ctx, rc, "region table rejected");
+  if (d_ws == nullptr) return fail(ctx, R3_EINVAL, "workspace is NULL");
+  if (reinterpret_cast<uintptr_t>(d_ws) & 255u) return fail(ctx, R3_EALIGN, "workspace not 256-byte aligned");
+  r3::TablePlan plan;
+  r3::plan_table(host_tbl, n, &plan);
+  if (plan.max_region_tiles > 0xFFFFFFu) return fail(ctx, R3_EINVAL, "region too large");
+  const r3::WorkspaceLayout lay = r3::workspace_layout(n, plan.tiles.size());
+  if (ws_bytes < lay.total) return fail(ctx, R3_ENOSPC, "workspace smaller than the table needs");
+
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return fail(ctx, R3_EHIP, "cannot select the device");
+  uint8_t* ws = static_cast<uint8_t*>(d_ws);
+  hipError_t e = hipMemset(ws + lay.ticket, 0, 256);
+  if (e == hipSuccess) e = hipMemcpy(ws + lay.regions, host_tbl, (size_t)n * sizeof(r3_region), hipMemcpyHostToDevice);
+  if (e == hipSuccess)
+    e = hipMemcpy(ws + lay.tile_begin, plan.tile_begin.data(), plan.tile_begin.size() * sizeof(uint64_t),
+                  hipMemcpyHostToDevice);
+  if (e == hipSuccess && !plan.tiles.empty())
+    e = hipMemcpy(ws + lay.tiles, plan.tiles.data(), plan.tiles.size() * sizeof(r3::Tile),
+                  hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) return fail_hip(ctx, e, "table upload");
+
+  r3_table* tbl = new (std::nothrow) r3_table();
+  if (tbl == nullptr) return fail(ctx, R3_ENOSPC, "out of host memory");
+  tbl->ctx = ctx;
+  tbl->arena_bytes = arena_bytes;
+  tbl->total_bytes = plan.total_bytes;
+  tbl->dev.ticket = reinterpret_cast<uint32_t*>(ws + lay.ticket);
+  tbl->dev.regions = reinterpret_cast<const r3_region*>(ws + lay.regions);
+  tbl->dev.tile_begin = reinterpret_cast<const uint64_t*>(ws + lay.tile_begin);
+  tbl->dev.tiles = reinterpret_cast<const r3::Tile*>(ws + lay.tiles);
+  tbl->dev.partials = reinterpret_cast<r3::Partial*>(ws + lay.partials);
+  tbl->dev.summaries = reinterpret_cast<r3_summary*>(ws + lay.summaries);
+  tbl->dev.n_regions = n;
+  tbl->dev.min_shift = plan.min_shift;
+  tbl->dev.cap_log2 = plan.cap_log2;
+  tbl->dev.max_region_tiles = plan.max_region_tiles;
+  tbl->dev.n_tiles = plan.tiles.size();
+  *out = tbl;
+  return R3_OK;
+}
+
+int r3_table_destroy(r3_table* tbl) {
+  if (tbl == nullptr) return R3_EINVAL;
+  delete tbl;
+  return R3_OK;
+}
+
+int r3_table_info(const r3_table* tbl, uint32_t* n_regions, uint64_t* n_tiles, uint32_t* tile_bytes,
+                  uint64_t* total_bytes, uint64_t* arena_bytes) {
+  if (tbl == nullptr) return R3_EINVAL;
+  if (n_regions) *n_regions = tbl->dev.n_regions;
+  if (n_tiles) *n_tiles = tbl->dev.n_tiles;
+  if (tile_bytes) *tile_bytes = 1u << tbl->dev.min_shift;
+  if (total_bytes) *total_bytes = tbl->total_bytes;
+  if (arena_bytes) *arena_bytes = tbl->arena_bytes;
+  return R3_OK;
+}
+
+int r3_restore(r3_ctx* ctx, const r3_table* tbl, const void* d_snapshot, void* d_live, void* stream) {
+  int rc = check_common(ctx, tbl);
+  if (rc != R3_OK) return rc;
+  if (d_snapshot == nullptr || d_live == nullptr) return fail(ctx, R3_EINVAL, "arena pointer is NULL");
+  if (!aligned16(d_snapshot) || !aligned16(d_live)) return fail(ctx, R3_EALIGN, "arena base not 16-byte aligned");
+  const uint8_t* s = static_cast<const uint8_t*>(d_snapshot);
+  const uint8_t* l = static_cast<const uint8_t*>(d_live);
+  if (s < l + tbl->arena_bytes && l < s + tbl->arena_bytes && tbl->arena_bytes)
+    return fail(ctx, R3_EINVAL, "snapshot and live arenas overlap");
+  DeviceGuard guard(ctx->device);
+  hipError_t e = r3::launch_restore(tbl->dev, d_snapshot, d_live, as_stream(stream));
+  return e == hipSuccess ? R3_OK : fail_hip(ctx, e, "restore launch");
+}
+
+int r3_checksum(r3_ctx* ctx, const r3_table* tbl, const void* d_arena, uint64_t* d_out, void* stream) {
+  int rc = check_common(ctx, tbl);
+  if (rc != R3_OK) return rc;
+  if (d_arena == nullptr || d_out == nullptr) return fail(ctx, R3_EINVAL, "pointer is NULL");
+  if (!aligned16(d_arena)) return fail(ctx, R3_EALIGN, "arena base not 16-byte aligned");
+  DeviceGuard guard(ctx->device);
+  hipError_t e = r3::launch_checksum(tbl->dev, d_arena, d_out, as_stream(stream));
+  return e == hipSuccess ? R3_OK : fail_hip(ctx, e, "checksum launch");
+}
+
+int r3_compare(r3_ctx* ctx, const r3_table* tbl, const void* d_live, const void* d_golden,
+               r3_region_result* d_out, r3_summary* d_summary, void* stream) {
+  int rc = check_common(ctx, tbl);
+  if (rc != R3_OK) return rc;
+  if (d_live == nullptr || d_golden == nullptr || d_out == nullptr)
+    return fail(ctx, R3_EINVAL, "pointer is NULL");
+  if (!aligned16(d_live) || !aligned16(d_golden)) return fail(ctx, R3_EALIGN, "arena base not 16-byte aligned");
+  DeviceGuard guard(ctx->device);
+  hipError_t e = r3::launch_compare(tbl->dev, d_live, d_golden, d_out, d_summary, as_stream(stream));
+  return e == hipSuccess ? R3_OK : fail_hip(ctx, e, "compare launch");
+}
+
+static bool page_ok(uint32_t page_bytes) {
+  return page_bytes >= 256 && page_bytes <= (1u << 20) && (page_bytes & (page_bytes - 1)) == 0;
+}
+
+int r3_dirty_diff(r3_ctx* ctx, const void* d_pre, const void* d_post, uint64_t bytes,
+                  uint32_t page_bytes, uint64_t* d_bitmap, uint64_t* d_dirty_count, void* stream) {
+  if (ctx == nullptr) return R3_EINVAL;
+  ctx->err.clear();
+  if (!page_ok(page_bytes)) return fail(ctx, R3_EINVAL, "page_bytes must be a power of two in 256..1 MiB");
+  if (bytes && (d_pre == nullptr || d_post == nullptr || d_bitmap == nullptr))
+    return fail(ctx, R3_EINVAL, "pointer is NULL");
+  if (!aligned16(d_pre) || !aligned16(d_post)) return fail(ctx, R3_EALIGN, "state base not 16-byte aligned");
+  if (reinterpret_cast<uintptr_t>(d_bitmap) & 7u) return fail(ctx, R3_EALIGN, "bitmap not 8-byte aligned");
+  DeviceGuard guard(ctx->device);
+  hipError_t e = r3::launch_dirty_diff(d_pre, d_post, bytes, page_bytes, d_bitmap, d_dirty_count,
+                                       as_stream(stream));
+  return e == hipSuccess ? R3_OK : fail_hip(ctx, e, "dirty-diff launch");
+}
+
+int r3_record(r3_ctx* ctx, const r3_table* tbl, void* d_live, r3_launch_fn launch, void* user,
+              void* d_prologue, void* d_epilogue, uint32_t page_bytes, uint64_t* d_bitmap,
+              uint64_t* d_dirty_count, uint64_t* d_pro_cs, uint64_t* d_epi_cs, void* stream) {
+  int rc = check_common(ctx, tbl);
+  if (rc != R3_OK) return rc;
+  if (d_live == nullptr || d_prologue == nullptr || d_epilogue == nullptr || launch == nullptr)
+    return fail(ctx, R3_EINVAL, "pointer is NULL");
+  if (!aligned16(d_live) || !aligned16(d_prologue) || !aligned16(d_epilogue))
+    return fail(ctx, R3_EALIGN, "arena base not 16-byte aligned");
+  if (d_bitmap && !page_ok(page_bytes)) return fail(ctx, R3_EINVAL, "page_bytes must be a power of two in 256..1 MiB");
+  if (d_dirty_count && !d_bitmap) return fail(ctx, R3_EINVAL, "dirty count needs the bitmap");
+  DeviceGuard guard(ctx->device);
+  hipStream_t s = as_stream(stream);
+  const uint64_t n = tbl->arena_bytes;
+  hipError_t e = r3::launch_copy_flat(d_live, d_prologue, n, s);
+  if (e != hipSuccess) return fail_hip(ctx, e, "prologue copy");
+  const int cand = launch(user, d_live, stream);
+  hipError_t le = hipGetLastError();
+  if (cand != 0 || le != hipSuccess) {
+    (void)hipStreamSynchronize(s);
+    return fail(ctx, R3_ECANDIDATE, "the recorded kernel failed to launch");
+  }
+  e = r3::launch_copy_flat(d_live, d_epilogue, n, s);
+  if (e == hipSuccess && d_bitmap)
+    e = r3::launch_dirty_diff(d_prologue, d_epilogue, n, page_bytes, d_bitmap, d_dirty_count, s);
+  if (e == hipSuccess && d_pro_cs) e = r3::launch_checksum(tbl->dev, d_prologue, d_pro_cs, s);
+  if (e == hipSuccess && d_epi_cs) e = r3::launch_checksum(tbl->dev, d_epilogue, d_epi_cs, s);
+  if (e != hipSuccess) return fail_hip(ctx, e, "record launch");
+  e = hipStreamSynchronize(s);
+  return e == hipSuccess ? R3_OK : fail_hip(ctx, e, "record wait");
+}
+
+int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
+                      const r3_table* check_tbl, const void* d_epilogue, void* d_live,
+                      r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
+                      uint32_t compare_policy, r3_region_result* d_regions,
+                      r3_eval_result* host_out, void* stream) {
+  int rc = check_common(ctx, restore_tbl);
+  if (rc == R3_OK) rc = check_common(ctx, check_tbl);
+  if (rc != R3_OK) return rc;
+  if (d_prologue == nullptr || d_epilogue == nullptr || d_live == nullptr || d_regions == nullptr ||
+      host_out == nullptr)
+    return fail(ctx, R3_EINVAL, "pointer is NULL");
+  if (!aligned16(d_prologue) || !aligned16(d_epilogue) || !aligned16(d_live))
+    return fail(ctx, R3_EALIGN, "arena base not 16-byte aligned");
+  if (compare_policy > R3_POLICY_LAST) return fail(ctx, R3_EINVAL, "unknown compare policy");
+  const uint64_t total = (uint64_t)warmup + reps;
+  if (reps == 0) return fail(ctx, R3_EINVAL, "reps must be at least 1");
+  if (total > R3_MAX_REPLAYS) return fail(ctx, R3_ENOSPC, "warmup + reps exceeds R3_MAX_REPLAYS");
+
+  DeviceGuard guard(ctx->device);
+  hipStream_t s = as_stream(stream);
+  while (ctx->events.size() < 2 * total) {
+    hipEvent_t ev;
+    hipError_t e = hipEventCreate(&ev);
+    if (e != hipSuccess) return fail_hip(ctx, e, "event create");
+    ctx->events.push_back(ev);
+  }
+
+  std::memset(host_out, 0, sizeof(*host_out));
+  host_out->first_index = R3_NO_INDEX;
+  host_out->first_region = R3_NO_REGION;
+
+  uint32_t n_validated = 0;
+  int cand = 0;
+  hipError_t e = hipSuccess;
+  uint32_t done = 0;
+  for (uint32_t rep = 0; rep < total; ++rep) {
+    e = r3::launch_restore(restore_tbl->dev, d_prologue, d_live, s);
+    if (e != hipSuccess) break;
+    if (launch) {
+      e = hipEventRecord(ctx->events[2 * rep], s);
+      if (e != hipSuccess) break;
+      cand = launch(user, d_live, stream);
+      hipError_t le = hipGetLastError();
+      if (cand == 0 && le != hipSuccess) cand = -(int)le;
+      if (cand != 0) break;
+      e = hipEventRecord(ctx->events[2 * rep + 1], s);
+      if (e != hipSuccess) break;
+    }
+    const bool validate = compare_policy == R3_POLICY_EVERY ||
+                          (compare_policy == R3_POLICY_FIRST && rep == 0) ||
+                          (compare_policy == R3_POLICY_LAST && rep == total - 1);
+    if (validate) {
+      e = r3::launch_compare(check_tbl->dev, d_live, d_epilogue, d_regions,
+                             &check_tbl->dev.summaries[n_validated], s);
+      if (e != hipSuccess) break;
+      ++n_validated;
+    }
+    ++done;
+  }
+  if (e == hipSuccess && n_validated)
+    e = hipMemcpyAsync(ctx->pinned, check_tbl->dev.summaries, n_validated * sizeof(r3_summary),
+                       hipMemcpyDeviceToHost, s);
+  hipError_t we = hipStreamSynchronize(s);
+  if (e == hipSuccess) e = we;
+  if (e != hipSuccess) return fail_hip(ctx, e, "replay loop");
+
+  host_out->candidate_status = cand;
+  for (uint32_t i = 0; i < n_validated; ++i)
+    host_out->total_mismatch = std::max(host_out->total_mismatch, ctx->pinned[i].total_mismatch);
+  if (n_validated) {
+    const r3_summary& last = ctx->pinned[n_validated - 1];
+    host_out->first_index = last.first_index;
+    host_out->first_region = last.first_region;
+    host_out->max_abs_err = last.max_abs_err;
+    host_out->max_rel_err = last.max_rel_err;
+  }
+  host_out->pass = (cand == 0 && host_out->total_mismatch == 0) ? 1u : 0u;
+
+  // Candidate times of the replays after the warm-up that ran to the end.
+  if (launch) {
+    std::vector<float> ms;
+    for (uint32_t rep = warmup; rep < done; ++rep) {
+      float t = 0.f;
+      if (hipEventElapsedTime(&t, ctx->events[2 * rep], ctx->events[2 * rep + 1]) == hipSuccess)
+        ms.push_back(t);
+    }
+    if (!ms.empty()) {
+      std::sort(ms.begin(), ms.end());
+      host_out->ms_min = ms.front();
+      host_out->ms_max = ms.back();
+      host_out->ms_median = ms.size() % 2 ? ms[ms.size() / 2]
+                                          : 0.5f * (ms[ms.size() / 2 - 1] + ms[ms.size() / 2]);
+    }
+  }
+  if (cand != 0) return fail(ctx, R3_ECANDIDATE, "the candidate failed to launch");
+  return R3_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,114 @@
+// Internal declarations shared by the host side and the kernels of libr3.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "r3.h"
+
+namespace r3 {
+
+constexpr uint64_t kPhi = 0x9E3779B97F4A7C15ull;  // floor(2^64 * (sqrt(5)-1)/2)
+constexpr uint64_t kLen = 0xBB67AE8584CAA73Bull;  // floor(2^64 * frac(sqrt(3)))
+
+constexpr int kWaveSize = 64;
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlock = kWaveSize * kWavesPerBlock;
+
+// A tile is the unit of work of one wavefront: up to 2^shift consecutive bytes of one
+// region, starting at a multiple of 2^shift from the region's first byte.  The shift is
+// a function of the region's size (tile_shift below): small regions use the minimum
+// tile, large ones grow so that no region has more than 2^cap_log2 tiles, which bounds
+// the per-region finalize pass.
+struct Tile {
+  uint32_t region;
+  uint32_t packed;  // bits 0..23: tile number inside the region; bits 24..31: shift
+};
+
+__host__ __device__ inline uint32_t tile_shift(uint64_t bytes, uint32_t min_shift,
+                                               uint32_t cap_log2) {
+  uint64_t q = (bytes + ((1ull << cap_log2) - 1)) >> cap_log2;  // ceil(bytes / cap)
+  uint32_t s = 0;
+  while (s < 63 && (1ull << s) < q) ++s;  // ceil(log2(q)), at most ~40 steps, scalar
+  return s < min_shift ? min_shift : s;
+}
+
+// What one wavefront leaves behind for the per-region finalize pass.
+struct Partial {
+  uint64_t count;
+  uint64_t first;  // region-relative element index, R3_NO_INDEX if none
+  uint64_t max_abs_bits;
+  uint64_t max_rel_bits;
+  uint64_t cks;  // sum of word products only; the length term is added at finalize
+};
+static_assert(sizeof(Partial) == 40, "partial layout");
+static_assert(sizeof(r3_region) == 40 && sizeof(r3_region_result) == 40, "ABI layout");
+static_assert(sizeof(r3_summary) == 40 && sizeof(r3_eval_result) == 56, "ABI layout");
+
+// Device-side view of a table's workspace.
+struct TableDev {
+  uint32_t* ticket;           // finalize blocks done so far in the call in flight
+  const r3_region* regions;   // n
+  const uint64_t* tile_begin; // n + 1, prefix sum of tiles per region
+  const Tile* tiles;          // n_tiles
+  Partial* partials;          // n_tiles (checksum-only calls use the first 8 bytes * n_tiles)
+  r3_summary* summaries;      // R3_MAX_REPLAYS slots for r3_eval_candidate
+  uint32_t n_regions;
+  uint32_t min_shift;         // log2 of the smallest tile
+  uint32_t cap_log2;          // log2 of the most tiles a region may have
+  uint32_t max_region_tiles;  // largest tile count of any region (sizes the finalize block)
+  uint64_t n_tiles;
+};
+
+// Host-side plan of a table: how the regions split into tiles.
+struct TablePlan {
+  uint32_t min_shift = 0, cap_log2 = 0, max_region_tiles = 0;
+  uint64_t total_bytes = 0;
+  std::vector<uint64_t> tile_begin;  // n + 1
+  std::vector<Tile> tiles;
+};
+
+struct WorkspaceLayout {
+  size_t ticket, regions, tile_begin, tiles, partials, summaries, total;
+};
+
+struct Tuning {
+  uint32_t min_shift;  // default 12 (4 KiB)
+  uint32_t cap_log2;   // default 13 (8192 tiles per region)
+};
+
+uint32_t elem_size(uint32_t dtype);  // 0 for an unknown dtype
+Tuning tuning();
+uint64_t max_tiles(uint32_t n, uint64_t arena_bytes);
+uint64_t count_tiles(const r3_region* t, uint32_t n);
+WorkspaceLayout workspace_layout(uint32_t n, uint64_t tiles);
+int validate_table(const r3_region* t, uint32_t n, uint64_t arena_bytes);
+void plan_table(const r3_region* t, uint32_t n, TablePlan* plan);
+
+// Kernel launchers (r3_kernels.hip).  All enqueue on `s` and return the launch status.
+hipError_t launch_restore(const TableDev& t, const void* src, void* dst, hipStream_t s);
+hipError_t launch_copy_flat(const void* src, void* dst, uint64_t bytes, hipStream_t s);
+hipError_t launch_checksum(const TableDev& t, const void* arena, uint64_t* out, hipStream_t s);
+hipError_t launch_compare(const TableDev& t, const void* live, const void* golden,
+                          r3_region_result* out, r3_summary* summary, hipStream_t s);
+hipError_t launch_dirty_diff(const void* pre, const void* post, uint64_t bytes, uint32_t page_bytes,
+                             uint64_t* bitmap, uint64_t* dirty_count, hipStream_t s);
+
+}  // namespace r3
+
+struct r3_ctx {
+  int device = 0;
+  std::string err;
+  r3_summary* pinned = nullptr;  // R3_MAX_REPLAYS summaries, pinned host memory
+  std::vector<hipEvent_t> events;  // 2 per replay, grown on demand
+};
+
+struct r3_table {
+  r3_ctx* ctx = nullptr;
+  r3::TableDev dev{};
+  uint64_t arena_bytes = 0;
+  uint64_t total_bytes = 0;
+};

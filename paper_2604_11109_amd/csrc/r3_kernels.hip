@@ -1,0 +1,797 @@
+// Device code of libr3.so for gfx950: batched restore, checksum, fused compare+checksum,
+// page dirty-diff and their small finalize passes.
+//
+// Everything here is a byte stream bounded by HBM bandwidth; there is no contraction, so no
+// MFMA.  The common shape: one wavefront (64 lanes) owns one tile of one region, walks it
+// with 16-byte loads per lane (1 KiB per wavefront instruction, several in flight), keeps
+// its running results in registers, combines them across the wavefront with lane
+// exchanges, and leaves one small partial per tile.  A second, tiny launch folds the
+// partials of every region (integer sums mod 2^64, min, max of non-negative doubles: all
+// independent of order, so the results are bit-exact however the tiles were scheduled).
+//
+// Floating point in the validation follows the rule in r3.h: binary64, one rounding per
+// operation.  This file is compiled with -ffp-contract=off; the pragma below repeats that.
+#include "r3_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace r3 {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kUnroll = 4;                       // 16-byte loads in flight per lane and stream
+constexpr uint64_t kVecKeyStep = 128ull * kPhi;  // 64 lanes * 2 words per 16-byte vector
+constexpr double kInf = __builtin_huge_val();
+constexpr double kGateShrink = 0x1.ffffffffffff8p-1;  // 1 - 2^-50
+constexpr double kGateFloor = 0x1p-1000;
+
+__device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
+
+__device__ __forceinline__ uint32_t wave_in_block() {
+  return __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+}
+
+__device__ __forceinline__ uint64_t wave_sum(uint64_t v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_min(uint32_t v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    uint32_t o = __shfl_xor(v, m, 64);
+    v = o < v ? o : v;
+  }
+  return v;
+}
+__device__ __forceinline__ uint64_t wave_min(uint64_t v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    uint64_t o = __shfl_xor(v, m, 64);
+    v = o < v ? o : v;
+  }
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_or(uint32_t v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v |= __shfl_xor(v, m, 64);
+  return v;
+}
+// Maximum of non-negative doubles (never NaN here): the order of their bit patterns.
+__device__ __forceinline__ uint64_t wave_max(uint64_t v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    uint64_t o = __shfl_xor(v, m, 64);
+    v = o > v ? o : v;
+  }
+  return v;
+}
+
+__device__ __forceinline__ uint64_t dbits(double d) { return (uint64_t)__double_as_longlong(d); }
+__device__ __forceinline__ double bits_d(uint64_t u) { return __longlong_as_double((long long)u); }
+
+// One checksum term: word w under key k.
+__device__ __forceinline__ uint64_t cks_term(uint32_t lo, uint32_t hi, uint64_t k) {
+  uint32_t a = lo + (uint32_t)k;
+  uint32_t b = hi + (uint32_t)(k >> 32);
+  return (uint64_t)a * (uint64_t)b;
+}
+
+// The tile a wavefront owns, resolved from the table (all values wavefront-uniform).
+struct TileView {
+  uint64_t rel_start;  // first byte of the tile, relative to the region
+  uint32_t len;        // bytes in the tile
+  uint32_t region;
+  uint64_t offset;     // region offset in the arena
+  uint64_t bytes;      // region size
+  uint32_t dtype, mode;
+  double rtol, atol;
+};
+
+__device__ __forceinline__ uint32_t sgpr(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ uint64_t sgpr(uint64_t v) {
+  return ((uint64_t)sgpr((uint32_t)(v >> 32)) << 32) | sgpr((uint32_t)v);
+}
+
+__device__ __forceinline__ TileView resolve_tile(const TableDev& t, uint64_t tile_id) {
+  TileView v;
+  Tile tl = t.tiles[tile_id];
+  v.region = sgpr(tl.region);
+  const uint32_t packed = sgpr(tl.packed);
+  const uint32_t index = packed & 0xFFFFFFu, shift = packed >> 24;
+  const r3_region* rg = &t.regions[v.region];
+  v.offset = sgpr(rg->offset);
+  v.bytes = sgpr(rg->bytes);
+  v.dtype = sgpr(rg->dtype);
+  v.mode = sgpr(rg->mode);
+  v.rtol = bits_d(sgpr(dbits(rg->rtol)));
+  v.atol = bits_d(sgpr(dbits(rg->atol)));
+  v.rel_start = (uint64_t)index << shift;
+  uint64_t left = v.bytes - v.rel_start;
+  uint64_t full = 1ull << shift;
+  v.len = (uint32_t)(left < full ? left : full);
+  return v;
+}
+
+// ---------------------------------------------------------------------------------------
+// Word loads for the paths that cannot use 16-byte vectors: region tails and regions whose
+// offset is not a multiple of 16.  ES = element size; p is ES-aligned; `valid` (1..8, a
+// multiple of ES) bytes belong to the region, the rest of the word reads as zero.
+// ---------------------------------------------------------------------------------------
+template <int ES>
+__device__ __forceinline__ uint64_t load_word(const uint8_t* p, uint32_t valid) {
+  uint64_t w = 0;
+  if (ES == 8) {
+    w = *(const uint64_t*)p;
+  } else if (ES == 4) {
+    w = *(const uint32_t*)p;
+    if (valid > 4) w |= (uint64_t)(*(const uint32_t*)(p + 4)) << 32;
+  } else if (ES == 2) {
+#pragma unroll
+    for (uint32_t b = 0; b < 8; b += 2)
+      if (b < valid) w |= (uint64_t)(*(const uint16_t*)(p + b)) << (8 * b);
+  } else {
+#pragma unroll
+    for (uint32_t b = 0; b < 8; ++b)
+      if (b < valid) w |= (uint64_t)p[b] << (8 * b);
+  }
+  return w;
+}
+
+// =======================================================================================
+// Restore / copy
+// =======================================================================================
+// Copies `len` bytes from src to dst (same misalignment on both sides because the arenas
+// are 16-byte aligned and share offsets): a head up to the next 16-byte boundary, 16-byte
+// vectors, a tail.  Head and tail move in units of `es` bytes (the element size, which
+// divides offset and length).
+__device__ __forceinline__ void copy_span(const uint8_t* src, uint8_t* dst, uint32_t len,
+                                          uint32_t es, uint32_t lane) {
+  uint32_t head = (uint32_t)((16 - ((uintptr_t)src & 15)) & 15);
+  if (head > len) head = len;
+  if (head) {
+    for (uint32_t b = lane * es; b < head; b += 64 * es) {
+      if (es == 1) dst[b] = src[b];
+      else if (es == 2) *(uint16_t*)(dst + b) = *(const uint16_t*)(src + b);
+      else if (es == 4) *(uint32_t*)(dst + b) = *(const uint32_t*)(src + b);
+      else *(uint64_t*)(dst + b) = *(const uint64_t*)(src + b);
+    }
+  }
+  const u32x4* s = (const u32x4*)(src + head);
+  u32x4* d = (u32x4*)(dst + head);
+  const uint32_t nvec = (len - head) >> 4;
+  uint32_t v = lane;
+  const uint32_t nfull = nvec / (64 * kUnroll);
+  for (uint32_t it = 0; it < nfull; ++it) {
+    u32x4 r[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) r[u] = __builtin_nontemporal_load(s + v + 64 * u);
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) __builtin_nontemporal_store(r[u], d + v + 64 * u);
+    v += 64 * kUnroll;
+  }
+  for (; v < nvec; v += 64) __builtin_nontemporal_store(__builtin_nontemporal_load(s + v), d + v);
+  const uint32_t done = head + (nvec << 4);
+  for (uint32_t b = done + lane * es; b < len; b += 64 * es) {
+    if (es == 1) dst[b] = src[b];
+    else if (es == 2) *(uint16_t*)(dst + b) = *(const uint16_t*)(src + b);
+    else if (es == 4) *(uint32_t*)(dst + b) = *(const uint32_t*)(src + b);
+    else *(uint64_t*)(dst + b) = *(const uint64_t*)(src + b);
+  }
+}
+
+__device__ __forceinline__ uint32_t elem_size_dev(uint32_t dtype) {
+  return dtype == R3_U8 ? 1u : dtype == R3_BF16 ? 2u : dtype == R3_F64 ? 8u : 4u;
+}
+
+__global__ __launch_bounds__(kBlock) void restore_kernel(TableDev t, const uint8_t* src,
+                                                         uint8_t* dst) {
+  const uint64_t tile_id = (uint64_t)blockIdx.x * kWavesPerBlock + wave_in_block();
+  if (tile_id >= t.n_tiles) return;
+  const TileView tv = resolve_tile(t, tile_id);
+  const uint64_t at = tv.offset + tv.rel_start;
+  copy_span(src + at, dst + at, tv.len, elem_size_dev(tv.dtype), lane_id());
+}
+
+// Whole-range copy for r3_record: tile k is bytes [k << shift, ...).
+__global__ __launch_bounds__(kBlock) void copy_flat_kernel(const uint8_t* src, uint8_t* dst,
+                                                           uint64_t bytes, uint32_t shift,
+                                                           uint64_t n_tiles) {
+  const uint64_t tile_id = (uint64_t)blockIdx.x * kWavesPerBlock + wave_in_block();
+  if (tile_id >= n_tiles) return;
+  const uint64_t at = tile_id << shift;
+  const uint64_t left = bytes - at;
+  const uint32_t len = (uint32_t)(left < (1ull << shift) ? left : (1ull << shift));
+  copy_span(src + at, dst + at, len, 1, lane_id());
+}
+
+// =======================================================================================
+// Checksum
+// =======================================================================================
+// Sum of the word terms of one tile.  word0 = region word index of the tile's first word.
+template <int ES>
+__device__ __forceinline__ uint64_t checksum_tile(const uint8_t* base, uint32_t len,
+                                                  uint64_t word0, uint32_t lane) {
+  uint64_t acc = 0;
+  if (((uintptr_t)base & 15) == 0) {
+    const u32x4* p = (const u32x4*)base;
+    const uint32_t nvec = len >> 4;
+    uint64_t k = (word0 + 2ull * lane + 1) * kPhi;
+    uint32_t v = lane;
+    const uint32_t nfull = nvec / (64 * kUnroll);
+    for (uint32_t it = 0; it < nfull; ++it) {
+      u32x4 r[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) r[u] = __builtin_nontemporal_load(p + v + 64 * u);
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const uint64_t ku = k + (uint64_t)u * kVecKeyStep;
+        acc += cks_term(r[u].x, r[u].y, ku);
+        acc += cks_term(r[u].z, r[u].w, ku + kPhi);
+      }
+      v += 64 * kUnroll;
+      k += (uint64_t)kUnroll * kVecKeyStep;
+    }
+    for (; v < nvec; v += 64) {
+      u32x4 r = __builtin_nontemporal_load(p + v);
+      acc += cks_term(r.x, r.y, k);
+      acc += cks_term(r.z, r.w, k + kPhi);
+      k += kVecKeyStep;
+    }
+    // Fewer than 16 bytes left: at most two words, the last one possibly partial.
+    const uint32_t tail = len & 15;
+    const uint32_t tail_words = (tail + 7) >> 3;
+    if (lane < tail_words) {
+      const uint32_t at = (nvec << 4) + 8 * lane;
+      const uint32_t valid = (len - at) < 8 ? (len - at) : 8;
+      uint64_t w = load_word<ES>(base + at, valid);
+      acc += cks_term((uint32_t)w, (uint32_t)(w >> 32), (word0 + 2ull * nvec + lane + 1) * kPhi);
+    }
+  } else {
+    const uint32_t nwords = (len + 7) >> 3;
+    for (uint32_t j = lane; j < nwords; j += 64) {
+      const uint32_t at = 8 * j;
+      const uint32_t valid = (len - at) < 8 ? (len - at) : 8;
+      uint64_t w = load_word<ES>(base + at, valid);
+      acc += cks_term((uint32_t)w, (uint32_t)(w >> 32), (word0 + j + 1) * kPhi);
+    }
+  }
+  return acc;
+}
+
+__global__ __launch_bounds__(kBlock) void checksum_kernel(TableDev t, const uint8_t* arena) {
+  const uint64_t tile_id = (uint64_t)blockIdx.x * kWavesPerBlock + wave_in_block();
+  if (tile_id >= t.n_tiles) return;
+  const TileView tv = resolve_tile(t, tile_id);
+  const uint8_t* base = arena + tv.offset + tv.rel_start;
+  const uint64_t word0 = tv.rel_start >> 3;  // tiles start at multiples of 16 bytes
+  const uint32_t lane = lane_id();
+  uint64_t acc;
+  switch (elem_size_dev(tv.dtype)) {
+    case 1: acc = checksum_tile<1>(base, tv.len, word0, lane); break;
+    case 2: acc = checksum_tile<2>(base, tv.len, word0, lane); break;
+    case 4: acc = checksum_tile<4>(base, tv.len, word0, lane); break;
+    default: acc = checksum_tile<8>(base, tv.len, word0, lane); break;
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) ((uint64_t*)t.partials)[tile_id] = acc;
+}
+
+// One block per region: add up the tile sums, add the length term.
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void checksum_finalize_kernel(TableDev t, uint64_t* out) {
+  __shared__ uint64_t sh[BLOCK / 64];
+  const uint32_t r = blockIdx.x;
+  const uint64_t b = t.tile_begin[r], e = t.tile_begin[r + 1];
+  const uint64_t* part = (const uint64_t*)t.partials;
+  uint64_t acc = 0;
+  for (uint64_t i = b + threadIdx.x; i < e; i += BLOCK) acc += part[i];
+  acc = wave_sum(acc);
+  if (BLOCK > 64) {
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      acc = 0;
+      for (int w = 0; w < BLOCK / 64; ++w) acc += sh[w];
+    }
+  }
+  if (threadIdx.x == 0) out[r] = acc + t.regions[r].bytes * kLen;
+}
+
+// =======================================================================================
+// Fused compare + checksum
+// =======================================================================================
+struct Acc {
+  uint32_t count;  // mismatches in this lane
+  uint32_t first;  // smallest mismatching element index inside the tile, ~0u if none
+  double max_abs;
+  double max_rel;
+  double gate;     // wavefront-uniform lower bound of the running max_rel, shrunk by 2^-50
+  uint64_t cks;
+};
+
+template <int DT> struct Elem;
+template <> struct Elem<R3_U8>   { static constexpr int size = 1; static constexpr bool is_float = false; };
+template <> struct Elem<R3_F32>  { static constexpr int size = 4; static constexpr bool is_float = true; };
+template <> struct Elem<R3_F64>  { static constexpr int size = 8; static constexpr bool is_float = true; };
+template <> struct Elem<R3_I32>  { static constexpr int size = 4; static constexpr bool is_float = false; };
+template <> struct Elem<R3_BF16> { static constexpr int size = 2; static constexpr bool is_float = true; };
+
+template <int DT>
+__device__ __forceinline__ double to_f64(uint64_t bits) {
+  if (DT == R3_U8) return (double)(uint32_t)bits;
+  if (DT == R3_I32) return (double)(int32_t)(uint32_t)bits;
+  if (DT == R3_F32) return (double)__uint_as_float((uint32_t)bits);
+  if (DT == R3_BF16) return (double)__uint_as_float((uint32_t)bits << 16);
+  return bits_d(bits);
+}
+
+// One element whose bit patterns differ.  Returns true when this lane's max_rel grew.
+//
+// The quotient d/|G| is needed only when it can exceed the running maximum.  With
+// gate <= max_rel*(1-2^-50) known for the whole wavefront and p = fl(gate*|G|) a normal
+// number, d <= p implies d < max_rel*|G| exactly, hence fl(d/|G|) <= max_rel: the divide
+// is skipped.  Any other case (p tiny, zero, NaN) takes the divide.
+template <int DT>
+__device__ __forceinline__ bool differing_elem(uint64_t cb, uint64_t gb, uint32_t idx, bool tol,
+                                               double rtol, double atol, Acc& a) {
+  const double C = to_f64<DT>(cb), G = to_f64<DT>(gb);
+  bool grew = false, mis;
+  double d;
+  const double aC = __builtin_fabs(C), aG = __builtin_fabs(G);
+  if (Elem<DT>::is_float && !(aC < kInf && aG < kInf)) {  // NaN or infinity on either side
+    d = kInf;
+    mis = true;
+    if (!(a.max_rel == kInf)) {
+      a.max_rel = kInf;
+      grew = true;
+    }
+  } else {
+    d = __builtin_fabs(C - G);
+    if (tol) {
+      const double t = rtol * aG;
+      const double thr = atol + t;
+      mis = d > thr;
+    } else {
+      mis = true;
+    }
+    const double p = a.gate * aG;
+    if (!(d <= p && p >= kGateFloor)) {
+      const double r = (G == 0.0) ? 0.0 : d / aG;
+      if (r > a.max_rel) {
+        a.max_rel = r;
+        grew = true;
+      }
+    }
+  }
+  a.max_abs = d > a.max_abs ? d : a.max_abs;
+  a.count += mis ? 1u : 0u;
+  const uint32_t cand = mis ? idx : 0xFFFFFFFFu;
+  a.first = cand < a.first ? cand : a.first;
+  return grew;
+}
+
+// One 64-bit word of live (wc) and golden (wg) data holding `nvalid` elements; idx = tile
+// index of its first element.
+template <int DT>
+__device__ __forceinline__ bool differing_word(uint64_t wc, uint64_t wg, uint32_t nvalid,
+                                               uint32_t idx, bool tol, double rtol, double atol,
+                                               Acc& a) {
+  constexpr int ES = Elem<DT>::size;
+  constexpr int EPW = 8 / ES;
+  bool grew = false;
+  if (wc == wg) return false;
+  if constexpr (ES == 8) {
+    grew = differing_elem<DT>(wc, wg, idx, tol, rtol, atol, a);
+  } else {
+    constexpr uint64_t mask = (1ull << (8 * (ES & 7))) - 1;
+#pragma unroll 2
+    for (int e = 0; e < EPW; ++e) {
+      const uint64_t cb = (wc >> (8 * ES * e)) & mask;
+      const uint64_t gb = (wg >> (8 * ES * e)) & mask;
+      if ((uint32_t)e < nvalid && cb != gb)
+        grew |= differing_elem<DT>(cb, gb, idx + e, tol, rtol, atol, a);
+    }
+  }
+  return grew;
+}
+
+// Refresh the wavefront-wide gate after some lane's max_rel grew.  Called by all lanes.
+__device__ __forceinline__ void refresh_gate(bool grew, Acc& a) {
+  if (__builtin_amdgcn_ballot_w64(grew) != 0) {
+    const double m = bits_d(wave_max(dbits(a.max_rel)));
+    a.gate = m * kGateShrink;
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ bool compare_vec(u32x4 c, u32x4 g, uint64_t k, uint32_t vec_index,
+                                            bool tol, double rtol, double atol, Acc& a) {
+  constexpr int EPW = 8 / Elem<DT>::size;
+  a.cks += cks_term(c.x, c.y, k);
+  a.cks += cks_term(c.z, c.w, k + kPhi);
+  const uint32_t diff = (c.x ^ g.x) | (c.y ^ g.y) | (c.z ^ g.z) | (c.w ^ g.w);
+  bool grew = false;
+  if (diff) {
+    const uint32_t idx = vec_index * (2 * EPW);
+    grew = differing_word<DT>(((uint64_t)c.y << 32) | c.x, ((uint64_t)g.y << 32) | g.x, EPW, idx,
+                              tol, rtol, atol, a);
+    grew |= differing_word<DT>(((uint64_t)c.w << 32) | c.z, ((uint64_t)g.w << 32) | g.z, EPW,
+                               idx + EPW, tol, rtol, atol, a);
+  }
+  return grew;
+}
+
+template <int DT>
+__device__ __forceinline__ void compare_tile(const uint8_t* cbase, const uint8_t* gbase,
+                                             uint32_t len, uint64_t word0, bool tol, double rtol,
+                                             double atol, uint32_t lane, Acc& a) {
+  constexpr int ES = Elem<DT>::size;
+  constexpr int EPW = 8 / ES;
+  if (((uintptr_t)cbase & 15) == 0) {
+    const u32x4* C = (const u32x4*)cbase;
+    const u32x4* G = (const u32x4*)gbase;
+    const uint32_t nvec = len >> 4;
+    uint64_t k = (word0 + 2ull * lane + 1) * kPhi;
+    uint32_t v = lane;
+    const uint32_t nfull = nvec / (64 * kUnroll);
+    for (uint32_t it = 0; it < nfull; ++it) {
+      u32x4 c[kUnroll], g[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        c[u] = __builtin_nontemporal_load(C + v + 64 * u);
+        g[u] = __builtin_nontemporal_load(G + v + 64 * u);
+      }
+      bool grew = false;
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u)
+        grew |= compare_vec<DT>(c[u], g[u], k + (uint64_t)u * kVecKeyStep, v + 64 * u, tol, rtol,
+                                atol, a);
+      refresh_gate(grew, a);
+      v += 64 * kUnroll;
+      k += (uint64_t)kUnroll * kVecKeyStep;
+    }
+    // Remaining whole vectors: same trip count for all lanes so that the gate refresh stays
+    // a wavefront-wide operation.
+    const uint32_t rest = nvec - nfull * 64 * kUnroll;
+    const uint32_t trips = (rest + 63) >> 6;
+    for (uint32_t it = 0; it < trips; ++it) {
+      bool grew = false;
+      if (v < nvec) {
+        u32x4 c = __builtin_nontemporal_load(C + v);
+        u32x4 g = __builtin_nontemporal_load(G + v);
+        grew = compare_vec<DT>(c, g, k, v, tol, rtol, atol, a);
+      }
+      refresh_gate(grew, a);
+      v += 64;
+      k += kVecKeyStep;
+    }
+    const uint32_t tail = len & 15;
+    const uint32_t tail_words = (tail + 7) >> 3;
+    bool grew = false;
+    if (lane < tail_words) {
+      const uint32_t at = (nvec << 4) + 8 * lane;
+      const uint32_t valid = (len - at) < 8 ? (len - at) : 8;
+      const uint64_t wc = load_word<ES>(cbase + at, valid);
+      const uint64_t wg = load_word<ES>(gbase + at, valid);
+      a.cks += cks_term((uint32_t)wc, (uint32_t)(wc >> 32), (word0 + 2ull * nvec + lane + 1) * kPhi);
+      grew = differing_word<DT>(wc, wg, valid / ES, at / ES, tol, rtol, atol, a);
+    }
+    refresh_gate(grew, a);
+  } else {
+    const uint32_t nwords = (len + 7) >> 3;
+    const uint32_t trips = (nwords + 63) >> 6;
+    uint32_t j = lane;
+    for (uint32_t it = 0; it < trips; ++it, j += 64) {
+      bool grew = false;
+      if (j < nwords) {
+        const uint32_t at = 8 * j;
+        const uint32_t valid = (len - at) < 8 ? (len - at) : 8;
+        const uint64_t wc = load_word<ES>(cbase + at, valid);
+        const uint64_t wg = load_word<ES>(gbase + at, valid);
+        a.cks += cks_term((uint32_t)wc, (uint32_t)(wc >> 32), (word0 + j + 1) * kPhi);
+        grew = differing_word<DT>(wc, wg, valid / ES, j * EPW, tol, rtol, atol, a);
+      }
+      refresh_gate(grew, a);
+    }
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void compare_kernel(TableDev t, const uint8_t* live,
+                                                         const uint8_t* golden) {
+  const uint64_t tile_id = (uint64_t)blockIdx.x * kWavesPerBlock + wave_in_block();
+  if (tile_id >= t.n_tiles) return;
+  const TileView tv = resolve_tile(t, tile_id);
+  const uint64_t at = tv.offset + tv.rel_start;
+  const uint8_t* c = live + at;
+  const uint8_t* g = golden + at;
+  const uint64_t word0 = tv.rel_start >> 3;
+  const bool tol = tv.mode == R3_CMP_TOL;
+  const uint32_t lane = lane_id();
+  Acc a;
+  a.count = 0;
+  a.first = 0xFFFFFFFFu;
+  a.max_abs = 0.0;
+  a.max_rel = 0.0;
+  a.gate = 0.0;
+  a.cks = 0;
+  switch (tv.dtype) {
+    case R3_U8:   compare_tile<R3_U8>(c, g, tv.len, word0, tol, tv.rtol, tv.atol, lane, a); break;
+    case R3_F32:  compare_tile<R3_F32>(c, g, tv.len, word0, tol, tv.rtol, tv.atol, lane, a); break;
+    case R3_F64:  compare_tile<R3_F64>(c, g, tv.len, word0, tol, tv.rtol, tv.atol, lane, a); break;
+    case R3_I32:  compare_tile<R3_I32>(c, g, tv.len, word0, tol, tv.rtol, tv.atol, lane, a); break;
+    default:      compare_tile<R3_BF16>(c, g, tv.len, word0, tol, tv.rtol, tv.atol, lane, a); break;
+  }
+  const uint64_t count = wave_sum(a.count);
+  const uint32_t first = wave_min(a.first);
+  const uint64_t max_abs = wave_max(dbits(a.max_abs));
+  const uint64_t max_rel = wave_max(dbits(a.max_rel));
+  const uint64_t cks = wave_sum(a.cks);
+  const uint64_t first_elem =
+      first == 0xFFFFFFFFu ? R3_NO_INDEX : tv.rel_start / elem_size_dev(tv.dtype) + first;
+  uint64_t* out = (uint64_t*)&t.partials[tile_id];
+  if (lane < 5) {
+    const uint64_t val = lane == 0 ? count : lane == 1 ? first_elem : lane == 2 ? max_abs
+                       : lane == 3 ? max_rel : cks;
+    out[lane] = val;
+  }
+}
+
+// One block per region folds that region's partials into its r3_region_result; the block
+// that finishes last (a ticket taken after a device-wide fence) folds the results of all
+// regions into the table summary and re-arms the ticket.
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void compare_finalize_kernel(TableDev t, r3_region_result* out,
+                                                                 r3_summary* summary) {
+  constexpr int NW = BLOCK / 64;
+  __shared__ uint64_t sh[5][NW];
+  __shared__ uint32_t sh_first_region[NW];
+  __shared__ bool is_last;
+  const uint32_t r = blockIdx.x;
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  {
+    const uint64_t b = t.tile_begin[r], e = t.tile_begin[r + 1];
+    uint64_t count = 0, first = R3_NO_INDEX, max_abs = 0, max_rel = 0, cks = 0;
+    for (uint64_t i = b + tid; i < e; i += BLOCK) {
+      const uint64_t* p = (const uint64_t*)&t.partials[i];
+      count += p[0];
+      first = p[1] < first ? p[1] : first;
+      max_abs = p[2] > max_abs ? p[2] : max_abs;
+      max_rel = p[3] > max_rel ? p[3] : max_rel;
+      cks += p[4];
+    }
+    count = wave_sum(count);
+    first = wave_min(first);
+    max_abs = wave_max(max_abs);
+    max_rel = wave_max(max_rel);
+    cks = wave_sum(cks);
+    if (NW > 1) {
+      if (lane == 0) {
+        sh[0][wave] = count; sh[1][wave] = first; sh[2][wave] = max_abs;
+        sh[3][wave] = max_rel; sh[4][wave] = cks;
+      }
+      __syncthreads();
+      if (tid == 0) {
+        count = 0; first = R3_NO_INDEX; max_abs = 0; max_rel = 0; cks = 0;
+        for (int w = 0; w < NW; ++w) {
+          count += sh[0][w];
+          first = sh[1][w] < first ? sh[1][w] : first;
+          max_abs = sh[2][w] > max_abs ? sh[2][w] : max_abs;
+          max_rel = sh[3][w] > max_rel ? sh[3][w] : max_rel;
+          cks += sh[4][w];
+        }
+      }
+    }
+    if (tid == 0) {
+      uint64_t* o = (uint64_t*)&out[r];
+      o[0] = count;
+      o[1] = first;
+      o[2] = max_abs;
+      o[3] = max_rel;
+      o[4] = cks + t.regions[r].bytes * kLen;
+    }
+  }
+  if (summary == nullptr) return;
+  if (tid == 0) {
+    __threadfence();  // this block's result is visible device-wide before the ticket moves
+    const uint32_t prev = __hip_atomic_fetch_add(t.ticket, 1u, __ATOMIC_ACQ_REL,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+    is_last = prev == gridDim.x - 1;
+  }
+  __syncthreads();
+  if (!is_last) return;
+  __threadfence();  // acquire side: drop anything cached before the other blocks' results
+  uint64_t total = 0, max_abs = 0, max_rel = 0;
+  uint32_t first_region = R3_NO_REGION;
+  for (uint32_t i = tid; i < t.n_regions; i += BLOCK) {
+    const uint64_t* o = (const uint64_t*)&out[i];
+    const uint64_t cnt = __builtin_nontemporal_load(o + 0);
+    total += cnt;
+    if (cnt != 0 && i < first_region) first_region = i;
+    const uint64_t ma = __builtin_nontemporal_load(o + 2), mr = __builtin_nontemporal_load(o + 3);
+    max_abs = ma > max_abs ? ma : max_abs;
+    max_rel = mr > max_rel ? mr : max_rel;
+  }
+  total = wave_sum(total);
+  first_region = wave_min(first_region);
+  max_abs = wave_max(max_abs);
+  max_rel = wave_max(max_rel);
+  if (NW > 1) {
+    __syncthreads();
+    if (lane == 0) {
+      sh[0][wave] = total; sh[2][wave] = max_abs; sh[3][wave] = max_rel;
+      sh_first_region[wave] = first_region;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      total = 0; max_abs = 0; max_rel = 0; first_region = R3_NO_REGION;
+      for (int w = 0; w < NW; ++w) {
+        total += sh[0][w];
+        max_abs = sh[2][w] > max_abs ? sh[2][w] : max_abs;
+        max_rel = sh[3][w] > max_rel ? sh[3][w] : max_rel;
+        first_region = sh_first_region[w] < first_region ? sh_first_region[w] : first_region;
+      }
+    }
+  }
+  if (tid == 0) {
+    summary->total_mismatch = total;
+    summary->first_region = first_region;
+    summary->first_index = first_region == R3_NO_REGION
+                               ? R3_NO_INDEX
+                               : __builtin_nontemporal_load((const uint64_t*)&out[first_region] + 1);
+    summary->pass = total == 0 ? 1u : 0u;
+    summary->max_abs_err = bits_d(max_abs);
+    summary->max_rel_err = bits_d(max_rel);
+    *t.ticket = 0;
+  }
+}
+
+// =======================================================================================
+// Page dirty-diff
+// =======================================================================================
+// One wavefront owns 16 consecutive pages (one 16-bit slice of a bitmap word) and ORs the
+// per-page "differs" flags of its lanes.  vec_shift = log2(page_bytes / 16).
+__global__ __launch_bounds__(kBlock) void dirty_diff_kernel(const uint8_t* pre, const uint8_t* post,
+                                                            uint64_t bytes, uint32_t page_shift,
+                                                            uint16_t* bitmap16, uint64_t n_slices) {
+  const uint64_t slice = (uint64_t)blockIdx.x * kWavesPerBlock + wave_in_block();
+  if (slice >= n_slices) return;
+  const uint32_t lane = lane_id();
+  const uint64_t span_start = (slice * 16) << page_shift;
+  uint32_t bits = 0;
+  if (span_start < bytes) {
+    const uint64_t span_full = 16ull << page_shift;
+    const uint64_t left = bytes - span_start;
+    const uint64_t span = left < span_full ? left : span_full;
+    const u32x4* A = (const u32x4*)(pre + span_start);
+    const u32x4* B = (const u32x4*)(post + span_start);
+    const uint32_t vec_shift = page_shift - 4;
+    const uint32_t nvec = (uint32_t)(span >> 4);
+    uint32_t v = lane;
+    const uint32_t nfull = nvec / (64 * kUnroll);
+    for (uint32_t it = 0; it < nfull; ++it) {
+      u32x4 a[kUnroll], b[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        a[u] = __builtin_nontemporal_load(A + v + 64 * u);
+        b[u] = __builtin_nontemporal_load(B + v + 64 * u);
+      }
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const uint32_t d = (a[u].x ^ b[u].x) | (a[u].y ^ b[u].y) | (a[u].z ^ b[u].z) | (a[u].w ^ b[u].w);
+        bits |= (d != 0 ? 1u : 0u) << ((v + 64 * u) >> vec_shift);
+      }
+      v += 64 * kUnroll;
+    }
+    for (; v < nvec; v += 64) {
+      const u32x4 a = __builtin_nontemporal_load(A + v), b = __builtin_nontemporal_load(B + v);
+      const uint32_t d = (a.x ^ b.x) | (a.y ^ b.y) | (a.z ^ b.z) | (a.w ^ b.w);
+      bits |= (d != 0 ? 1u : 0u) << (v >> vec_shift);
+    }
+    // Bytes after the last whole vector (only at the very end of the state).
+    const uint32_t done = nvec << 4;
+    const uint32_t tail = (uint32_t)(span - done);
+    if (lane < tail) {
+      const uint32_t at = done + lane;
+      bits |= (pre[span_start + at] != post[span_start + at] ? 1u : 0u) << (at >> page_shift);
+    }
+  }
+  bits = wave_or(bits);
+  if (lane == 0) bitmap16[slice] = (uint16_t)bits;
+}
+
+__global__ __launch_bounds__(kBlock) void popcount_kernel(const uint64_t* bitmap, uint64_t n_words,
+                                                          uint64_t* count) {
+  __shared__ uint64_t sh[kWavesPerBlock];
+  uint64_t acc = 0;
+  for (uint64_t i = threadIdx.x; i < n_words; i += kBlock) acc += __popcll(bitmap[i]);
+  acc = wave_sum(acc);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    acc = 0;
+    for (int w = 0; w < kWavesPerBlock; ++w) acc += sh[w];
+    *count = acc;
+  }
+}
+
+uint32_t grid_for(uint64_t tiles) { return (uint32_t)((tiles + kWavesPerBlock - 1) / kWavesPerBlock); }
+
+}  // namespace
+
+hipError_t launch_restore(const TableDev& t, const void* src, void* dst, hipStream_t s) {
+  if (t.n_tiles == 0) return hipSuccess;
+  restore_kernel<<<grid_for(t.n_tiles), kBlock, 0, s>>>(t, (const uint8_t*)src, (uint8_t*)dst);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy_flat(const void* src, void* dst, uint64_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  const uint32_t shift = tile_shift(bytes, 12, 14);
+  const uint64_t n_tiles = (bytes + ((1ull << shift) - 1)) >> shift;
+  copy_flat_kernel<<<grid_for(n_tiles), kBlock, 0, s>>>((const uint8_t*)src, (uint8_t*)dst, bytes,
+                                                        shift, n_tiles);
+  return hipGetLastError();
+}
+
+static int finalize_block(uint32_t max_region_tiles) {
+  return max_region_tiles <= 64 * 4 ? 64 : max_region_tiles <= 256 * 8 ? 256 : 1024;
+}
+
+hipError_t launch_checksum(const TableDev& t, const void* arena, uint64_t* out, hipStream_t s) {
+  if (t.n_tiles) {
+    checksum_kernel<<<grid_for(t.n_tiles), kBlock, 0, s>>>(t, (const uint8_t*)arena);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  switch (finalize_block(t.max_region_tiles)) {
+    case 64: checksum_finalize_kernel<64><<<t.n_regions, 64, 0, s>>>(t, out); break;
+    case 256: checksum_finalize_kernel<256><<<t.n_regions, 256, 0, s>>>(t, out); break;
+    default: checksum_finalize_kernel<1024><<<t.n_regions, 1024, 0, s>>>(t, out); break;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_compare(const TableDev& t, const void* live, const void* golden,
+                          r3_region_result* out, r3_summary* summary, hipStream_t s) {
+  if (t.n_tiles) {
+    compare_kernel<<<grid_for(t.n_tiles), kBlock, 0, s>>>(t, (const uint8_t*)live,
+                                                          (const uint8_t*)golden);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  switch (finalize_block(t.max_region_tiles)) {
+    case 64: compare_finalize_kernel<64><<<t.n_regions, 64, 0, s>>>(t, out, summary); break;
+    case 256: compare_finalize_kernel<256><<<t.n_regions, 256, 0, s>>>(t, out, summary); break;
+    default: compare_finalize_kernel<1024><<<t.n_regions, 1024, 0, s>>>(t, out, summary); break;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_dirty_diff(const void* pre, const void* post, uint64_t bytes, uint32_t page_bytes,
+                             uint64_t* bitmap, uint64_t* dirty_count, hipStream_t s) {
+  uint32_t page_shift = 0;
+  while ((1u << page_shift) < page_bytes) ++page_shift;
+  const uint64_t n_pages = (bytes + page_bytes - 1) >> page_shift;
+  const uint64_t n_words = (n_pages + 63) / 64;
+  const uint64_t n_slices = n_words * 4;
+  if (n_slices) {
+    dirty_diff_kernel<<<grid_for(n_slices), kBlock, 0, s>>>(
+        (const uint8_t*)pre, (const uint8_t*)post, bytes, page_shift, (uint16_t*)bitmap, n_slices);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  if (dirty_count) {
+    popcount_kernel<<<1, kBlock, 0, s>>>(bitmap, n_words, dirty_count);
+    return hipGetLastError();
+  }
+  return hipSuccess;
+}
+
+}  // namespace r3

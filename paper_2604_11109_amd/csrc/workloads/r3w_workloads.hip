@@ -1,0 +1,162 @@
+// Candidate kernels used to exercise the replay path: variants of a 7-point Jacobi sweep and
+// of a CSR sparse matrix-vector product, each behind a launch callback with the r3_launch_fn
+// signature.  They stand in for the application kernels whose recorded states the paper
+// replays (stencil and sparse kernels of its benchmark set, Section VII); they are the
+// thing being evaluated, not part of the evaluation path.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#pragma clang fp contract(off)
+
+extern "C" {
+
+// One Jacobi sweep on an n^3 fp64 grid stored x-fastest at in_off, written to out_off.
+// block: threads per block; unroll: points per thread; bug != 0: the x loop stops one
+// short, so points with x == n-2 keep their previous value.
+typedef struct {
+  uint64_t in_off, out_off;
+  uint32_t n, block, unroll, bug;
+} r3w_jacobi_args;
+
+// y = A x for a CSR matrix inside the arena.  rows_per_wave in {1,...,128} (power of two):
+// below 64, 64/rows_per_wave lanes share a row and combine with a butterfly; at 64 and 128
+// a lane walks 1 or 2 rows from first to last entry.  block: threads per block (multiple
+// of 64).
+typedef struct {
+  uint64_t rowptr_off, col_off, val_off, x_off, y_off;
+  uint32_t rows, rows_per_wave, block, reserved;
+} r3w_spmv_args;
+
+int r3w_jacobi_launch(void* user, void* d_live, void* stream);
+int r3w_spmv_launch(void* user, void* d_live, void* stream);
+int r3w_failing_launch(void* user, void* d_live, void* stream);
+}
+
+namespace {
+
+template <int UNROLL>
+__global__ void jacobi_kernel(const double* __restrict__ in, double* __restrict__ out, uint32_t n,
+                              uint32_t x_end, uint64_t total, uint64_t stride) {
+  const uint64_t n2 = (uint64_t)n * n;
+  uint64_t idx = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u, idx += stride) {
+    if (idx >= total) return;
+    const uint32_t x = (uint32_t)(idx % n);
+    const uint32_t y = (uint32_t)((idx / n) % n);
+    const uint32_t z = (uint32_t)(idx / n2);
+    if (x < 1 || x >= x_end || y < 1 || y >= n - 1 || z < 1 || z >= n - 1) continue;
+    double s = in[idx] + in[idx - 1];
+    s = s + in[idx + 1];
+    s = s + in[idx - n];
+    s = s + in[idx + n];
+    s = s + in[idx - n2];
+    s = s + in[idx + n2];
+    out[idx] = s * (1.0 / 7.0);
+  }
+}
+
+template <int LANES>  // lanes that share one row
+__global__ void spmv_shared_kernel(const int* __restrict__ rp, const int* __restrict__ ci,
+                                   const double* __restrict__ v, const double* __restrict__ x,
+                                   double* __restrict__ y, uint32_t rows) {
+  const uint64_t gid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const uint64_t row = gid / LANES;
+  const uint32_t sub = (uint32_t)(gid % LANES);
+  double s = 0.0;
+  if (row < rows) {
+    const int e = rp[row + 1];
+    for (int j = rp[row] + (int)sub; j < e; j += LANES) {
+      const double p = v[j] * x[ci[j]];
+      s = s + p;
+    }
+  }
+#pragma unroll
+  for (int m = LANES / 2; m >= 1; m >>= 1) s = s + __shfl_xor(s, m, 64);
+  if (row < rows && sub == 0) y[row] = s;
+}
+
+template <int ROWS>  // rows one lane walks
+__global__ void spmv_serial_kernel(const int* __restrict__ rp, const int* __restrict__ ci,
+                                   const double* __restrict__ v, const double* __restrict__ x,
+                                   double* __restrict__ y, uint32_t rows) {
+  const uint64_t gid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+#pragma unroll
+  for (int k = 0; k < ROWS; ++k) {
+    const uint64_t row = gid * ROWS + k;
+    if (row >= rows) return;
+    double s = 0.0;
+    const int e = rp[row + 1];
+    for (int j = rp[row]; j < e; ++j) {
+      const double p = v[j] * x[ci[j]];
+      s = s + p;
+    }
+    y[row] = s;
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+int r3w_jacobi_launch(void* user, void* d_live, void* stream) {
+  const r3w_jacobi_args* a = static_cast<const r3w_jacobi_args*>(user);
+  if (a == nullptr || d_live == nullptr || a->n < 3) return 1;
+  if (a->block == 0 || a->block > 1024 || (a->block & 63)) return 2;
+  if (a->unroll != 1 && a->unroll != 2 && a->unroll != 4) return 3;
+  if ((a->in_off | a->out_off) & 7) return 4;
+  const double* in = reinterpret_cast<const double*>(static_cast<uint8_t*>(d_live) + a->in_off);
+  double* out = reinterpret_cast<double*>(static_cast<uint8_t*>(d_live) + a->out_off);
+  const uint64_t total = (uint64_t)a->n * a->n * a->n;
+  const uint64_t threads = (total + a->unroll - 1) / a->unroll;
+  const uint32_t grid = (uint32_t)((threads + a->block - 1) / a->block);
+  const uint64_t stride = (uint64_t)grid * a->block;
+  const uint32_t x_end = a->bug ? a->n - 2 : a->n - 1;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  switch (a->unroll) {
+    case 1: jacobi_kernel<1><<<grid, a->block, 0, s>>>(in, out, a->n, x_end, total, stride); break;
+    case 2: jacobi_kernel<2><<<grid, a->block, 0, s>>>(in, out, a->n, x_end, total, stride); break;
+    default: jacobi_kernel<4><<<grid, a->block, 0, s>>>(in, out, a->n, x_end, total, stride); break;
+  }
+  return hipGetLastError() == hipSuccess ? 0 : 5;
+}
+
+int r3w_spmv_launch(void* user, void* d_live, void* stream) {
+  const r3w_spmv_args* a = static_cast<const r3w_spmv_args*>(user);
+  if (a == nullptr || d_live == nullptr || a->rows == 0) return 1;
+  if (a->block == 0 || a->block > 1024 || (a->block & 63)) return 2;
+  const uint32_t rpw = a->rows_per_wave;
+  if (rpw == 0 || rpw > 128 || (rpw & (rpw - 1))) return 3;
+  uint8_t* base = static_cast<uint8_t*>(d_live);
+  const int* rp = reinterpret_cast<const int*>(base + a->rowptr_off);
+  const int* ci = reinterpret_cast<const int*>(base + a->col_off);
+  const double* v = reinterpret_cast<const double*>(base + a->val_off);
+  const double* x = reinterpret_cast<const double*>(base + a->x_off);
+  double* y = reinterpret_cast<double*>(base + a->y_off);
+  const uint64_t rows_per_block = (uint64_t)(a->block / 64) * rpw;
+  const uint32_t grid = (uint32_t)((a->rows + rows_per_block - 1) / rows_per_block);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+#define SHARED(L) spmv_shared_kernel<L><<<grid, a->block, 0, s>>>(rp, ci, v, x, y, a->rows)
+  switch (rpw) {
+    case 1: SHARED(64); break;
+    case 2: SHARED(32); break;
+    case 4: SHARED(16); break;
+    case 8: SHARED(8); break;
+    case 16: SHARED(4); break;
+    case 32: SHARED(2); break;
+    case 64: spmv_serial_kernel<1><<<grid, a->block, 0, s>>>(rp, ci, v, x, y, a->rows); break;
+    default: spmv_serial_kernel<2><<<grid, a->block, 0, s>>>(rp, ci, v, x, y, a->rows); break;
+  }
+#undef SHARED
+  return hipGetLastError() == hipSuccess ? 0 : 5;
+}
+
+// A candidate that cannot be launched (the "fails to compile or crashes" class of Section
+// V-C, as far as a host can force it without faulting the GPU).
+int r3w_failing_launch(void* user, void* d_live, void* stream) {
+  (void)d_live;
+  (void)stream;
+  return user ? *static_cast<const int*>(user) : 77;
+}
+
+}  // extern "C"

@@ -1,0 +1,57 @@
+"""ctypes view of libr3_workloads.so: candidate kernels (Jacobi and CSR SpMV variants) behind
+launch callbacks that r3_record / r3_eval_candidate can call without leaving native code."""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libr3_workloads.so")
+_lib = None
+
+
+class JacobiArgs(ctypes.Structure):
+    _fields_ = [("in_off", ctypes.c_uint64), ("out_off", ctypes.c_uint64), ("n", ctypes.c_uint32),
+                ("block", ctypes.c_uint32), ("unroll", ctypes.c_uint32), ("bug", ctypes.c_uint32)]
+
+
+class SpmvArgs(ctypes.Structure):
+    _fields_ = [("rowptr_off", ctypes.c_uint64), ("col_off", ctypes.c_uint64),
+                ("val_off", ctypes.c_uint64), ("x_off", ctypes.c_uint64), ("y_off", ctypes.c_uint64),
+                ("rows", ctypes.c_uint32), ("rows_per_wave", ctypes.c_uint32),
+                ("block", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                "%s is missing: build it with `python -m paper_2604_11109_amd.build`" % LIB_PATH)
+        _lib = ctypes.CDLL(LIB_PATH)
+    return _lib
+
+
+def _addr(name):
+    return ctypes.cast(getattr(lib(), name), ctypes.c_void_p).value
+
+
+def jacobi_launch():
+    """Address of the Jacobi launch callback (pass as `launch`, with a JacobiArgs as `user`)."""
+    return _addr("r3w_jacobi_launch")
+
+
+def spmv_launch():
+    return _addr("r3w_spmv_launch")
+
+
+def failing_launch():
+    return _addr("r3w_failing_launch")
+
+
+def jacobi_args(case, block, unroll, bug):
+    return JacobiArgs(case["in_off"], case["out_off"], case["n"], block, unroll, bug)
+
+
+def spmv_args(case, rows_per_wave, block):
+    o = case["offsets"]
+    return SpmvArgs(o["row_ptr"], o["col_idx"], o["vals"], o["x"], o["y"], case["rows"],
+                    rows_per_wave, block, 0)

@@ -1,0 +1,326 @@
+"""GPU parity: every entry point of libr3.so, called through the C ABI, against the CPU
+oracle on the same seeded inputs.  Integer, index and checksum results must be equal;
+the fp64 error maxima must be equal bit for bit (the path computes them with the same
+IEEE operations in an order-free maximum, so the tolerance is zero)."""
+import struct
+
+import numpy as np
+import pytest
+
+import r3_inputs as ri
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2604_11109_amd import binding as r3
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    r3.lib()  # raises if the HIP library is not built: there is no fallback
+    ctx = r3.Context(0)
+    yield r3, ctx, torch
+    ctx.close()
+
+
+def dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def assert_results_equal(got, exp, what=""):
+    assert got.shape == exp.shape
+    for name in exp.dtype.names:
+        g = got[name].view(np.uint64) if got[name].dtype.kind == "f" else got[name]
+        e = exp[name].view(np.uint64) if exp[name].dtype.kind == "f" else exp[name]
+        bad = np.flatnonzero(g != e)
+        assert bad.size == 0, "%s field %s differs at %s: got %s expected %s" % (
+            what, name, bad[:5], got[name][bad[:5]], exp[name][bad[:5]])
+
+
+def run_compare(r3, ctx, torch, rows, live, golden, arena_bytes):
+    tbl = r3.Table(ctx, rows, arena_bytes)
+    d_out = torch.zeros(40 * max(tbl.n, 1), dtype=torch.uint8, device="cuda:0")
+    d_sum = torch.zeros(40, dtype=torch.uint8, device="cuda:0")
+    r3.r3_compare(ctx, tbl, live, golden, d_out, d_sum)
+    torch.cuda.synchronize()
+    return r3.results_to_numpy(d_out, tbl.n), r3.summary_to_numpy(d_sum)
+
+
+# ----------------------------------------------------------------------------------------
+# checksum and restore on many small regions (configs[2] shape, reduced and full)
+# ----------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n_regions,max_bytes,align", [(300, 1 << 18, 256), (300, 1 << 17, 1),
+                                                       (64, 1 << 21, 16), (4096, 1 << 20, 256)])
+def test_checksum_and_restore_many_regions(env, oracle, n_regions, max_bytes, align):
+    r3, ctx, torch = env
+    c = ri.many_regions(n_regions=n_regions, max_bytes=max_bytes, align=align, seed=1003 + align)
+    print("case many_regions", n_regions, max_bytes, align, c["arena_bytes"], flush=True)
+    otbl = oracle.make_table(c["rows"])
+    tbl = r3.Table(ctx, c["rows"], c["arena_bytes"])
+    d_snap, d_live = dev(torch, c["snapshot"]), dev(torch, c["live"])
+    d_cs = torch.zeros(tbl.n, dtype=torch.int64, device="cuda:0")
+    r3.r3_checksum(ctx, tbl, d_snap, d_cs)
+    torch.cuda.synchronize()
+    exp_cs = oracle.checksum(otbl, c["snapshot"])
+    got_cs = host(d_cs).view(np.uint64)
+    assert (got_cs == exp_cs).all(), np.flatnonzero(got_cs != exp_cs)[:10]
+    # restore: regions copied, gaps untouched, snapshot unchanged
+    r3.r3_restore(ctx, tbl, d_snap, d_live)
+    torch.cuda.synchronize()
+    exp_live = c["live"].copy()
+    oracle.restore(otbl, c["snapshot"], exp_live)
+    got_live = host(d_live)
+    assert (got_live == exp_live).all(), np.flatnonzero(got_live != exp_live)[:10]
+    assert (host(d_snap) == c["snapshot"]).all()
+    # invariant: restore then checksum reproduces the recorded checksums
+    d_cs2 = torch.zeros(tbl.n, dtype=torch.int64, device="cuda:0")
+    r3.r3_checksum(ctx, tbl, d_live, d_cs2)
+    torch.cuda.synchronize()
+    assert (host(d_cs2).view(np.uint64) == exp_cs).all()
+
+
+def test_checksum_edge_sizes(env, oracle):
+    r3, ctx, torch = env
+    rng = np.random.default_rng(21)
+    arena = rng.integers(0, 256, size=1 << 16, dtype=np.uint8)
+    sizes = [0, 1, 2, 7, 8, 9, 15, 16, 17, 31, 32, 33, 1023, 1024, 1025, 4095, 4096, 4097, 8191, 12289]
+    rows, at = [], 0
+    for s in sizes:
+        rows.append((at, s, ri.U8, ri.BITWISE, 0, 0))
+        at += (s + 15) // 16 * 16 + 16
+    rows.append((at + 3, 777, ri.U8, ri.BITWISE, 0, 0))      # odd offset
+    rows.append((at + 1024 + 2, 38, ri.BF16, ri.BITWISE, 0, 0))
+    rows.append((at + 2048 + 4, 44, ri.I32, ri.BITWISE, 0, 0))
+    rows.append((at + 3072 + 8, 808, ri.F64, ri.BITWISE, 0, 0))
+    tbl = r3.Table(ctx, rows, arena.size)
+    d_cs = torch.zeros(tbl.n, dtype=torch.int64, device="cuda:0")
+    r3.r3_checksum(ctx, tbl, dev(torch, arena), d_cs)
+    torch.cuda.synchronize()
+    exp = oracle.checksum(oracle.make_table(rows), arena)
+    assert (host(d_cs).view(np.uint64) == exp).all()
+
+
+# ----------------------------------------------------------------------------------------
+# fused compare + checksum
+# ----------------------------------------------------------------------------------------
+@pytest.mark.parametrize("seed,align", [(1, 16), (2, 16), (3, 1), (4, 1), (5, 256), (6, 1)])
+def test_compare_mixed_tables(env, oracle, seed, align):
+    r3, ctx, torch = env
+    c = ri.mixed_compare_case(seed, align=align, max_bytes=400000 if seed % 2 else 60000)
+    print("case mixed_compare", seed, align, c["arena_bytes"], flush=True)
+    exp_res, exp_sum = oracle.compare(oracle.make_table(c["rows"]), c["live"], c["golden"])
+    got_res, got_sum = run_compare(r3, ctx, torch, c["rows"], dev(torch, c["live"]),
+                                   dev(torch, c["golden"]), c["arena_bytes"])
+    assert_results_equal(got_res, exp_res, "regions")
+    assert_results_equal(got_sum, exp_sum, "summary")
+
+
+def test_compare_replay_small_full_size(env, oracle):
+    """configs[0] at full size: 1049 planted mismatches among one-step perturbations."""
+    r3, ctx, torch = env
+    c = ri.replay_small()
+    exp_res, exp_sum = oracle.compare(oracle.make_table(c["check_rows"]), c["live"], c["epilogue"])
+    got_res, got_sum = run_compare(r3, ctx, torch, c["check_rows"], dev(torch, c["live"]),
+                                   dev(torch, c["epilogue"]), c["arena_bytes"])
+    assert_results_equal(got_res, exp_res)
+    assert_results_equal(got_sum, exp_sum)
+    assert int(got_res[0]["mismatch_count"]) == c["n_planted"] == 1049
+    assert int(got_res[0]["first_mismatch"]) == int(c["planted"][0])
+
+
+def test_compare_self_and_single_perturbation(env, oracle):
+    r3, ctx, torch = env
+    rng = np.random.default_rng(31)
+    n = 300001
+    g = rng.standard_normal(n).astype("<f4")
+    rows = [(0, 4 * n, ri.F32, ri.TOL, 1e-5, 1e-7)]
+    arena_bytes = 4 * n + 12
+    gold = np.zeros(arena_bytes, np.uint8)
+    gold[:4 * n] = g.view(np.uint8)
+    res, summ = run_compare(r3, ctx, torch, rows, dev(torch, gold), dev(torch, gold), arena_bytes)
+    assert int(res[0]["mismatch_count"]) == 0 and int(res[0]["first_mismatch"]) == r3.NO_INDEX
+    assert res[0]["max_abs_err"].tobytes() == bytes(8) and res[0]["max_rel_err"].tobytes() == bytes(8)
+    assert int(summ[0]["pass"]) == 1 and int(summ[0]["first_region"]) == r3.NO_REGION
+    for q in [0, 1, 65, 4095, 4096, 123457, n - 2, n - 1]:
+        live = gold.copy()
+        live[4 * q:4 * q + 4] = np.frombuffer(np.float32(g[q] * 1.25 + 0.5).tobytes(), np.uint8)
+        exp_res, exp_sum = oracle.compare(oracle.make_table(rows), live, gold)
+        res, summ = run_compare(r3, ctx, torch, rows, dev(torch, live), dev(torch, gold), arena_bytes)
+        assert_results_equal(res, exp_res, "q=%d" % q)
+        assert_results_equal(summ, exp_sum, "q=%d" % q)
+        assert int(res[0]["mismatch_count"]) == 1 and int(res[0]["first_mismatch"]) == q
+
+
+def test_compare_rounding_witnesses(env, oracle):
+    """Cases where a fused multiply-add, a flushed subnormal or an inexact divide would show."""
+    from fractions import Fraction
+    r3, ctx, torch = env
+    rng = np.random.default_rng(41)
+    # (a) thresholds whose fused and unfused roundings differ, with d on the boundary
+    found = []
+    while len(found) < 40:
+        rtol, atol, G = float(rng.uniform(0.1, 1)), float(rng.uniform(0.1, 1)), float(rng.uniform(0.5, 2))
+        fused = float(Fraction(atol) + Fraction(rtol) * Fraction(G))
+        unfused = float(Fraction(atol) + Fraction(float(Fraction(rtol) * Fraction(G))))
+        if fused == unfused:
+            continue
+        c = G + max(fused, unfused)
+        d = float(abs(Fraction(c) - Fraction(G)))
+        if d == max(fused, unfused):
+            found.append((rtol, atol, G, c))
+    rows, live, gold = [], [], []
+    for i, (rtol, atol, G, c) in enumerate(found):
+        rows.append((16 * i, 8, ri.F64, ri.TOL, rtol, atol))
+        live.append(struct.pack("<dd", c, 0.0))
+        gold.append(struct.pack("<dd", G, 0.0))
+    live = np.frombuffer(b"".join(live), np.uint8).copy()
+    gold = np.frombuffer(b"".join(gold), np.uint8).copy()
+    exp_res, exp_sum = oracle.compare(oracle.make_table(rows), live, gold)
+    res, summ = run_compare(r3, ctx, torch, rows, dev(torch, live), dev(torch, gold), live.size)
+    assert_results_equal(res, exp_res, "unfused threshold")
+    assert 0 < int(exp_sum[0]["total_mismatch"]) < len(found)
+    # (b) subnormal fp32 / bf16 / fp64 values and their neighbours; (c) random quotients
+    n = 20000
+    f32 = rng.integers(0, 0x00800000, size=n, dtype=np.uint32) | (rng.integers(0, 2, n, dtype=np.uint32) << 31)
+    f32c = (f32.astype(np.int64) + rng.integers(-5, 6, n)).astype(np.uint32)
+    bf = rng.integers(0, 0x0080, size=n, dtype=np.uint16)
+    bfc = (bf.astype(np.int32) + rng.integers(-2, 3, n)).astype(np.uint16)
+    f64 = rng.integers(0, 1 << 52, size=n, dtype=np.uint64)
+    f64c = (f64.astype(np.int64) + rng.integers(-5, 6, n)).astype(np.uint64)
+    q_g = (rng.standard_normal(n) * np.exp(rng.uniform(-300, 300, n))).astype("<f8")
+    q_c = (q_g * (1 + rng.standard_normal(n) * 1e-3)).astype("<f8")
+    parts_g = [f32.view(np.uint8), bf.view(np.uint8), f64.view(np.uint8), q_g.view(np.uint8)]
+    parts_c = [f32c.view(np.uint8), bfc.view(np.uint8), f64c.view(np.uint8), q_c.view(np.uint8)]
+    dts = [ri.F32, ri.BF16, ri.F64, ri.F64]
+    rows, at = [], 0
+    for p, dt in zip(parts_g, dts):
+        rows.append((at, p.size, dt, ri.TOL, 1e-3, 1e-45))
+        at += (p.size + 255) // 256 * 256
+    gold = np.zeros(at, np.uint8)
+    live = np.zeros(at, np.uint8)
+    for (off, nb, *_), pg, pc in zip(rows, parts_g, parts_c):
+        gold[off:off + nb] = pg
+        live[off:off + nb] = pc
+    exp_res, exp_sum = oracle.compare(oracle.make_table(rows), live, gold)
+    res, summ = run_compare(r3, ctx, torch, rows, dev(torch, live), dev(torch, gold), at)
+    assert_results_equal(res, exp_res, "subnormals and quotients")
+    assert_results_equal(summ, exp_sum)
+    # every element its own region: no maximum can hide a wrong quotient
+    m = 3000
+    rows1 = [(rows[3][0] + 8 * i, 8, ri.F64, ri.TOL, 1e-3, 0.0) for i in range(m)]
+    exp_res, _ = oracle.compare(oracle.make_table(rows1), live, gold)
+    res, _ = run_compare(r3, ctx, torch, rows1, dev(torch, live), dev(torch, gold), at)
+    assert_results_equal(res, exp_res, "single-element regions")
+
+
+def test_compare_large_snapshot_reduced(env, oracle):
+    """configs[3] shape at 8 x 8 MiB: planted counts and first indices, checksums of live."""
+    r3, ctx, torch = env
+    c = ri.large_snapshot(n_regions=8, region_bytes=(8 << 20) + 4096 + 64, frac=1e-5)
+    exp_res, exp_sum = oracle.compare(oracle.make_table(c["rows"]), c["snapshot"], c["golden"])
+    res, summ = run_compare(r3, ctx, torch, c["rows"], dev(torch, c["snapshot"]), dev(torch, c["golden"]),
+                            c["arena_bytes"])
+    assert_results_equal(res, exp_res)
+    assert_results_equal(summ, exp_sum)
+    for r, idx in enumerate(c["planted"]):
+        assert int(res[r]["mismatch_count"]) == len(idx) and int(res[r]["first_mismatch"]) == int(idx[0])
+
+
+@pytest.mark.parametrize("min_tile,cap", [(1024, 64), (4096, 8192), (65536, 256), (1 << 20, 64)])
+def test_tile_shapes_do_not_change_results(env, oracle, min_tile, cap):
+    r3, ctx, torch = env
+    c = ri.mixed_compare_case(9, align=16, max_bytes=3000000)
+    exp_res, exp_sum = oracle.compare(oracle.make_table(c["rows"]), c["live"], c["golden"])
+    r3.r3_tune_tiles(min_tile, cap)
+    try:
+        res, summ = run_compare(r3, ctx, torch, c["rows"], dev(torch, c["live"]), dev(torch, c["golden"]),
+                                c["arena_bytes"])
+        tbl = r3.Table(ctx, c["rows"], c["arena_bytes"])
+        d_live = dev(torch, c["live"])
+        r3.r3_restore(ctx, tbl, dev(torch, c["golden"]), d_live)
+        d_cs = torch.zeros(tbl.n, dtype=torch.int64, device="cuda:0")
+        r3.r3_checksum(ctx, tbl, d_live, d_cs)
+        torch.cuda.synchronize()
+    finally:
+        r3.r3_tune_tiles(0, 0)
+    assert_results_equal(res, exp_res)
+    assert_results_equal(summ, exp_sum)
+    assert (host(d_cs).view(np.uint64) == oracle.checksum(oracle.make_table(c["rows"]), c["golden"])).all()
+
+
+# ----------------------------------------------------------------------------------------
+# dirty-diff
+# ----------------------------------------------------------------------------------------
+@pytest.mark.parametrize("nbytes,page", [(70 * 4096 + 123, 4096), (1 << 22, 4096), (5000, 256),
+                                         (3 * (1 << 20) + 17, 1 << 20), (1, 4096), (64 * 4096, 4096),
+                                         (64 * 4096 * 5 + 4095, 4096), (1 << 20, 65536)])
+def test_dirty_diff(env, oracle, nbytes, page):
+    r3, ctx, torch = env
+    rng = np.random.default_rng(nbytes % 1000 + page)
+    pre = rng.integers(0, 256, size=nbytes, dtype=np.uint8)
+    post = pre.copy()
+    k = min(nbytes, 50)
+    idx = rng.choice(nbytes, size=k, replace=False)
+    post[idx] ^= rng.integers(1, 256, size=k, dtype=np.uint8)
+    post[nbytes - 1] ^= 1
+    post[0] ^= 0x80
+    for a, b in [(pre, post), (pre, pre)]:
+        nw = r3.bitmap_words(nbytes, page)
+        d_bm = torch.full((nw + 2,), -1, dtype=torch.int64, device="cuda:0")
+        d_cnt = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+        r3.r3_dirty_diff(ctx, dev(torch, a), dev(torch, b), nbytes, page, d_bm, d_cnt)
+        torch.cuda.synchronize()
+        exp_bm, exp_cnt = oracle.dirty_diff(a, b, page)
+        got = host(d_bm).view(np.uint64)
+        assert (got[:nw] == exp_bm).all()
+        assert (got[nw:] == 0xFFFFFFFFFFFFFFFF).all()        # nothing written past the bitmap
+        assert int(host(d_cnt)[0]) == exp_cnt
+
+
+def test_dirty_diff_empty_and_errors(env):
+    r3, ctx, torch = env
+    d = torch.zeros(4096, dtype=torch.uint8, device="cuda:0")
+    bm = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+    cnt = torch.full((1,), 7, dtype=torch.int64, device="cuda:0")
+    r3.r3_dirty_diff(ctx, d, d, 0, 4096, bm, cnt)
+    torch.cuda.synchronize()
+    assert int(host(cnt)[0]) == 0
+    for bad_page in (0, 100, 128, 3000, 1 << 21):
+        with pytest.raises(r3.R3Error) as e:
+            r3.r3_dirty_diff(ctx, d, d, 4096, bad_page, bm, cnt)
+        assert e.value.status == r3.EINVAL
+
+
+# ----------------------------------------------------------------------------------------
+# error paths that the host decides (no kernel runs)
+# ----------------------------------------------------------------------------------------
+def test_host_rejections(env):
+    r3, ctx, torch = env
+    a = torch.zeros(4096 + 16, dtype=torch.uint8, device="cuda:0")
+    b = torch.zeros(4096 + 16, dtype=torch.uint8, device="cuda:0")
+    tbl = r3.Table(ctx, [(0, 1024, ri.F32, ri.BITWISE, 0, 0)], 4096)
+    out = torch.zeros(40, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(r3.R3Error) as e:
+        r3.r3_restore(ctx, tbl, a[1:], b)
+    assert e.value.status == r3.EALIGN
+    with pytest.raises(r3.R3Error) as e:
+        r3.r3_restore(ctx, tbl, a, a)
+    assert e.value.status == r3.EINVAL
+    with pytest.raises(r3.R3Error) as e:
+        r3.r3_compare(ctx, tbl, a.data_ptr(), 0, out)
+    assert e.value.status == r3.EINVAL
+    with pytest.raises(r3.R3Error) as e:
+        r3.Table(ctx, [(0, 1024, ri.F32, ri.BITWISE, 0, 0), (512, 1024, ri.F32, ri.BITWISE, 0, 0)], 4096)
+    assert e.value.status == r3.EOVERLAP
+    with pytest.raises(r3.R3Error) as e:
+        r3.Table(ctx, [], 4096)
+    assert e.value.status == r3.EINVAL
+    ctx2 = r3.Context(0)
+    with pytest.raises(r3.R3Error) as e:
+        r3.r3_restore(ctx2, tbl, a, b)
+    assert e.value.status == r3.EINVAL
+    ctx2.close()

@@ -1,0 +1,109 @@
+"""CPU-only: the C-ABI library loads, exports every declared symbol, and its host logic
+(table rules, workspace sizing) agrees with the oracle's statement of the rules."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def r3():
+    from paper_2604_11109_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2604_11109_amd import build
+        build.build_lib("libr3.so", verbose=False)
+    binding.lib()
+    return binding
+
+
+def test_exports_every_declared_symbol(r3):
+    header = open(os.path.join(ROOT, "include", "r3.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(r3_[a-z_0-9]+)\s*\(", header))
+    names -= {"r3_launch_fn"}
+    assert names == set(r3.DECLARED)
+    L = r3.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+    assert L.r3_version() == 1
+    assert r3.lib().r3_strerror(r3.EOVERLAP) == b"regions overlap"
+
+
+def test_struct_layouts_match_header(r3):
+    import ctypes
+    assert r3.REGION_DTYPE.itemsize == 40 and r3.RESULT_DTYPE.itemsize == 40
+    assert r3.SUMMARY_DTYPE.itemsize == 40 and ctypes.sizeof(r3.EvalResult) == 56
+    assert r3.REGION_DTYPE.fields["rtol"][1] == 24 and r3.RESULT_DTYPE.fields["checksum"][1] == 32
+
+
+def test_table_rules_agree_with_oracle(r3, oracle):
+    rng = np.random.default_rng(5)
+    fixed = [
+        ([(0, 64, 1, 1, 1e-5, 1e-7), (64, 64, 2, 0, 0, 0)], 128),
+        ([(0, 64, 1, 1, 1e-5, 1e-7), (64, 64, 2, 0, 0, 0)], 127),
+        ([(0, 64, 9, 0, 0, 0)], 128), ([(0, 64, 1, 7, 0, 0)], 128),
+        ([(0, 64, 1, 1, -1.0, 0)], 128), ([(0, 64, 1, 1, 0, float("nan"))], 128),
+        ([(0, 64, 1, 1, float("inf"), 0)], 128), ([(2, 64, 1, 0, 0, 0)], 128),
+        ([(4, 12, 2, 0, 0, 0)], 128), ([(2, 6, 4, 0, 0, 0)], 128), ([(3, 5, 0, 0, 0, 0)], 128),
+        ([(1 << 63, 1 << 63, 0, 0, 0, 0)], 128), ([(2**64 - 8, 16, 2, 0, 0, 0)], 2**64 - 1),
+        ([(0, 64, 1, 0, 0, 0), (60, 8, 1, 0, 0, 0)], 128),
+        ([(64, 64, 1, 0, 0, 0), (0, 64, 1, 0, 0, 0)], 128),
+        ([(0, 64, 1, 0, 0, 0), (32, 0, 1, 0, 0, 0)], 128),
+        ([(0, 64, 1, 0, 0, 0), (32, 64, 1, 0, 0, 0), (2, 4, 1, 0, 0, 0)], 128),
+        ([(0, 256, 1, 0, 0, 0), (2, 4, 1, 0, 0, 0)], 128),
+    ]
+    for rows, arena in fixed:
+        assert r3.r3_table_validate(r3.make_table(rows), arena) == oracle.validate_table(
+            oracle.make_table(rows), arena), rows
+    assert r3.r3_table_validate(None, 10) == oracle.validate_table(None, 10) == r3.EINVAL
+    # random tables, many of them broken in one way or another
+    seen = set()
+    for _ in range(3000):
+        n = int(rng.integers(1, 7))
+        rows = []
+        for _ in range(n):
+            dt = int(rng.choice([0, 1, 2, 3, 4, 4, 1, 5]))
+            es = {0: 1, 1: 4, 2: 8, 3: 4, 4: 2}.get(dt, 4)
+            off = int(rng.integers(0, 40)) * es + int(rng.random() < 0.05)
+            nb = int(rng.integers(0, 12)) * es + int(rng.random() < 0.05)
+            mode = int(rng.choice([0, 1, 1, 0, 2])) if rng.random() < 0.1 else int(rng.integers(0, 2))
+            rtol = float(rng.choice([0.0, 1e-5, -1e-9, np.nan, np.inf])) if rng.random() < 0.1 else 1e-6
+            rows.append((off, nb, dt, mode, rtol, 0.0))
+        arena = int(rng.integers(16, 400))
+        a = r3.r3_table_validate(r3.make_table(rows), arena)
+        b = oracle.validate_table(oracle.make_table(rows), arena)
+        assert a == b, (rows, arena)
+        seen.add(a)
+    assert seen == {0, -1, -2, -3, -4}
+
+
+def test_workspace_sizes(r3):
+    rows = r3.make_table([(0, 1 << 20, 1, 0, 0, 0), (1 << 20, 100, 0, 0, 0, 0), (1 << 21, 0, 2, 0, 0, 0)])
+    exact = r3.r3_table_workspace_bytes_exact(rows, 1 << 22)
+    bound = r3.r3_table_workspace_bytes(3, 1 << 22)
+    assert 0 < exact <= bound
+    assert r3.r3_table_workspace_bytes_exact(r3.make_table([(2, 4, 1, 0, 0, 0)]), 64) == 0
+    # the bound never falls below the exact need, whatever the split of the arena
+    rng = np.random.default_rng(6)
+    for _ in range(200):
+        n = int(rng.integers(1, 50))
+        arena = int(rng.integers(1, 1 << 26))
+        cuts = np.sort(rng.integers(0, arena + 1, size=2 * n))
+        rws = [(int(cuts[2 * i]), int(cuts[2 * i + 1] - cuts[2 * i]), 0, 0, 0, 0) for i in range(n)]
+        ex = r3.r3_table_workspace_bytes_exact(r3.make_table(rws), arena)
+        assert 0 < ex <= r3.r3_table_workspace_bytes(n, arena)
+    with pytest.raises(r3.R3Error):
+        r3.r3_tune_tiles(3000, 0)
+    r3.r3_tune_tiles(0, 0)
+
+
+def test_no_gpu_calls_fail_cleanly(r3):
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(r3.R3Error) as e:
+        r3.Context(0)
+    assert e.value.status == r3.EHIP
