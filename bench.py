@@ -1,0 +1,279 @@
+#!/usr/bin/env python3
+"""Benchmark of the replay-evaluation hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one candidate evaluation through r3_eval_candidate: batched restore of the
+recorded prologue, launch of the candidate kernel, fused compare+checksum against the
+recorded epilogue, summary back to the host.  Inputs (snapshots, golden state, tables) are
+resident in HBM before the timed region starts.  Prints ONE JSON line.
+
+Workloads (shapes of the five benchmark configurations):
+  jacobi          256^3 fp64 7-point Jacobi, 8 candidate variants (default)
+  replay_small    3 x 2^20 fp32 inputs + 2^20 fp32 output, pure restore -> validate replays
+  many_regions    4096 regions, 256 B .. 1 MiB, ~0.5 GiB: restore + validate the whole table
+  large_snapshot  16 x 2 GiB regions (fp32 / bf16), 32 GiB per arena
+  spmv            CSR SpMV, 2^21 rows x 27 nnz, 64 launch configurations
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=None)
+    p.add_argument("--warmup", type=int, default=None)
+    p.add_argument("--workload", default="jacobi",
+                   choices=["jacobi", "replay_small", "many_regions", "large_snapshot", "spmv"])
+    p.add_argument("--no-large", action="store_true", help="skip the extra large-snapshot leg")
+    p.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    return p.parse_args()
+
+
+class Replay:
+    """Everything one workload keeps resident: tables, snapshots, live arena, candidates."""
+
+    def __init__(self, name, r3, wl, ctx, torch):
+        import numpy as np
+
+        import r3_inputs as ri
+        self.name, self.r3, self.ctx, self.torch = name, r3, ctx, torch
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+        self.launch, self.candidates, self.expect_pass = None, [None], [None]
+        self.host_case = None
+        if name == "jacobi":
+            c = ri.jacobi(256)
+            A = c["arena_bytes"]
+            self.restore_tbl = r3.Table(ctx, c["restore_rows"], A)
+            self.check_tbl = r3.Table(ctx, [c["check_rows"][1]], A)
+            self.d_live = up(c["prologue"])
+            self.d_pro = torch.empty(A, dtype=torch.uint8, device="cuda:0")
+            self.d_epi = torch.empty(A, dtype=torch.uint8, device="cuda:0")
+            self.launch = wl.jacobi_launch()
+            base = wl.jacobi_args(c, 64, 1, 0)
+            r3.r3_record(ctx, self.restore_tbl, self.d_live, self.launch, base, self.d_pro, self.d_epi)
+            self.candidates = [wl.jacobi_args(c, b, u, g) for b, u, g in ri.JACOBI_VARIANTS]
+            self.expect_pass = [g == 0 for _, _, g in ri.JACOBI_VARIANTS]
+            self.host_case = c
+            self.desc = "7-point Jacobi 256^3 fp64, 8 candidate variants, restore 2x128 MiB, validate 128 MiB"
+        elif name == "replay_small":
+            c = ri.replay_small()
+            A = c["arena_bytes"]
+            self.restore_tbl = r3.Table(ctx, c["restore_rows"], A)
+            self.check_tbl = r3.Table(ctx, c["check_rows"], A)
+            self.d_pro, self.d_epi, self.d_live = up(c["prologue"]), up(c["epilogue"]), up(c["live"])
+            self.expect_pass = [False]
+            self.host_case = c
+            self.desc = "3 x 2^20 fp32 inputs restored, 2^20 fp32 output validated (rtol 1e-5, atol 1e-7)"
+        elif name == "many_regions":
+            c = ri.many_regions()
+            A = c["arena_bytes"]
+            self.restore_tbl = self.check_tbl = r3.Table(ctx, c["rows"], A)
+            self.d_pro = up(c["snapshot"])
+            self.d_epi = self.d_pro
+            self.d_live = up(c["live"])
+            self.expect_pass = [True]
+            self.desc = "4096 regions 256 B..1 MiB (fp32/fp64/int32/bf16), %.0f MiB, restore + validate" % (A / 2**20)
+        elif name == "large_snapshot":
+            c = ri.large_snapshot_device()
+            A = c["arena_bytes"]
+            self.restore_tbl = self.check_tbl = r3.Table(ctx, c["rows"], A)
+            self.d_pro, self.d_epi = c["snapshot"], c["golden"]
+            self.d_live = torch.empty(A, dtype=torch.uint8, device="cuda:0")
+            self.expect_pass = [False]
+            self.n_planted = sum(len(i) for i in c["planted"])
+            self.desc = "16 regions x 2 GiB (8 fp32, 8 bf16), restore 32 GiB + validate against golden"
+        elif name == "spmv":
+            c = ri.spmv()
+            A = c["arena_bytes"]
+            self.restore_tbl = r3.Table(ctx, c["table_rows"], A)
+            self.check_tbl = r3.Table(ctx, c["y_rows"], A)
+            self.d_live = up(c["prologue"])
+            self.d_pro = torch.empty(A, dtype=torch.uint8, device="cuda:0")
+            self.d_epi = torch.empty(A, dtype=torch.uint8, device="cuda:0")
+            self.launch = wl.spmv_launch()
+            r3.r3_record(ctx, self.restore_tbl, self.d_live, self.launch, wl.spmv_args(c, 64, 256),
+                         self.d_pro, self.d_epi)
+            self.candidates = [wl.spmv_args(c, r, b) for r, b in ri.SPMV_VARIANTS]
+            self.expect_pass = [True if r >= 64 else None for r, _ in ri.SPMV_VARIANTS]
+            self.desc = "CSR SpMV 2^21 rows x 27 nnz fp64, 64 launch configurations, full-arena restore 688 MiB"
+        self.arena_bytes = A
+        self.d_regions = torch.zeros(40 * self.check_tbl.n, dtype=torch.uint8, device="cuda:0")
+        self.restore_bytes = 2 * self.restore_tbl.info()["total_bytes"]
+        self.validate_bytes = 2 * self.check_tbl.info()["total_bytes"]
+
+    def step(self, i):
+        k = i % len(self.candidates)
+        rc, out = self.r3.r3_eval_candidate(self.ctx, self.restore_tbl, self.d_pro, self.check_tbl,
+                                            self.d_epi, self.d_live, self.launch, self.candidates[k],
+                                            0, 1, self.r3.EVERY, self.d_regions)
+        want = self.expect_pass[k]
+        if rc != 0 or (want is not None and bool(out.passed) != want):
+            raise RuntimeError("evaluation %d of %s gave pass=%d (expected %s), status %d"
+                               % (i, self.name, out.passed, want, rc))
+        return out
+
+
+def timed_run(rp, steps, warmup):
+    torch, ctx = rp.torch, rp.ctx
+    for i in range(warmup):
+        rp.step(i)
+    ctx.profile(True)
+    ctx.profile_read(reset=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        rp.step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = ctx.profile_read(reset=True)
+    ctx.profile(False)
+    return t1 - t0, prof
+
+
+def stage_report(rp, prof):
+    out = {}
+    if prof.restore_launches:
+        ms = prof.restore_ms / prof.restore_launches
+        out["restore"] = {"ms": ms, "algorithmic_bytes": rp.restore_bytes,
+                          "GB/s": rp.restore_bytes / ms / 1e6}
+    if prof.validate_launches:
+        ms = prof.validate_ms / prof.validate_launches
+        out["validate"] = {"ms": ms, "algorithmic_bytes": rp.validate_bytes,
+                           "GB/s": rp.validate_bytes / ms / 1e6}
+    if prof.candidate_launches:
+        out["candidate"] = {"ms": prof.candidate_ms / prof.candidate_launches}
+    if "restore" in out and "validate" in out:
+        tot_ms = out["restore"]["ms"] + out["validate"]["ms"]
+        tot_b = rp.restore_bytes + rp.validate_bytes
+        out["restore+validate"] = {"ms": tot_ms, "algorithmic_bytes": tot_b, "GB/s": tot_b / tot_ms / 1e6,
+                                   "frac_of_hbm_peak": tot_b / tot_ms / 1e6 / HBM_PEAK_GBS}
+    return out
+
+
+def roofline(rp, stages):
+    """The dominant kernel of the path: whichever of restore / validate takes longer."""
+    cands = [(k, stages[k]) for k in ("restore", "validate") if k in stages]
+    name, st = max(cands, key=lambda kv: kv[1]["ms"])
+    kernel = "restore_kernel" if name == "restore" else "compare_kernel (+finalize)"
+    ach = st["GB/s"]
+    return {"bound": "hbm", "kernel": kernel, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": ach / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_launch": st["algorithmic_bytes"],
+            "avg_launch_ms": st["ms"]}
+
+
+def cpu_baseline(rp):
+    """The CPU oracle, untuned, single thread, on a bounded sample of the same workload."""
+    import numpy as np
+
+    import r3_inputs as ri
+    from oracle import r3_oracle as o
+    if rp.name == "jacobi":
+        c = rp.host_case
+        n = c["n"]
+        pro = c["prologue"]
+        epi = rp.d_epi.cpu().numpy()
+        rt = o.make_table(c["restore_rows"])
+        ct = o.make_table([c["check_rows"][1]])
+        live = np.zeros_like(pro)
+
+        def sweep(a):
+            g = a[c["in_off"]:c["in_off"] + c["grid_bytes"]].view("<f8").reshape(n, n, n)
+            a[c["out_off"]:c["out_off"] + c["grid_bytes"]] = ri.jacobi_reference(g).reshape(-1).view(np.uint8)
+            return 0
+        evals = 0
+        t0 = time.perf_counter()
+        while True:
+            res = o.eval_candidate(rt, pro, ct, epi, live, sweep, 0, 1)
+            evals += 1
+            if time.perf_counter() - t0 > 10.0 or evals >= 8:
+                break
+        dt = time.perf_counter() - t0
+        assert res["pass"] == 1
+        return {"value": evals / dt, "unit": "evals/s", "cores": 1, "kind": "oracle",
+                "sample": "%d evaluations of the 256^3 Jacobi replay (oracle restore 256 MiB, numpy sweep as the "
+                          "candidate, oracle compare of the 128 MiB output)" % evals}
+    if rp.name == "replay_small":
+        c = rp.host_case
+        rt, ct = o.make_table(c["restore_rows"]), o.make_table(c["check_rows"])
+        live = c["live"].copy()
+        evals, t0 = 0, time.perf_counter()
+        while time.perf_counter() - t0 < 10.0:
+            o.eval_candidate(rt, c["prologue"], ct, c["epilogue"], live, None, 0, 1)
+            evals += 1
+        dt = time.perf_counter() - t0
+        return {"value": evals / dt, "unit": "evals/s", "cores": 1, "kind": "oracle",
+                "sample": "%d pure restore->validate replays at full size" % evals}
+    # generic: restore + compare of a 256 MiB slice of the first regions, scaled by bytes
+    return None
+
+
+def large_leg(r3, wl, ctx, torch):
+    free, _ = torch.cuda.mem_get_info()
+    if free < 110 * (1 << 30):
+        return {"skipped": "needs 96 GiB of free device memory, %.0f GiB free" % (free / 2**30)}
+    rp = Replay("large_snapshot", r3, wl, ctx, torch)
+    dt, prof = timed_run(rp, 3, 1)
+    st = stage_report(rp, prof)
+    out = {"workload": rp.desc, "steps": 3, "ms_per_step": dt / 3 * 1e3, "stages": st,
+           "roofline": roofline(rp, st)}
+    del rp
+    torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused)" % a.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2604_11109_amd import binding as r3
+    from paper_2604_11109_amd import workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    r3.lib()
+    wl.lib()
+    ctx = r3.Context(0)
+    defaults = {"jacobi": (200, 16), "replay_small": (2000, 100), "many_regions": (200, 10),
+                "large_snapshot": (5, 1), "spmv": (128, 8)}
+    steps = a.steps if a.steps is not None else defaults[a.workload][0]
+    warmup = a.warmup if a.warmup is not None else defaults[a.workload][1]
+
+    rp = Replay(a.workload, r3, wl, ctx, torch)
+    dt, prof = timed_run(rp, steps, warmup)
+    stages = stage_report(rp, prof)
+    line = {
+        "metric": "candidate evals/sec per kernel; restore+compare GB/s as % of HBM peak",
+        "value": steps / dt, "unit": "evals/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": dt / steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f64" if a.workload in ("jacobi", "spmv") else "u8",
+        "data": "synthetic",
+        "config": {"workload": "%s: %s" % (a.workload, rp.desc)},
+        "roofline": roofline(rp, stages),
+        "stages": stages,
+    }
+    cpu = None if a.no_cpu else cpu_baseline(rp)
+    line["cpu_baseline"] = cpu
+    del rp
+    torch.cuda.empty_cache()
+    if a.workload != "large_snapshot" and not a.no_large:
+        line["large_snapshot"] = large_leg(r3, wl, ctx, torch)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

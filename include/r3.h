@@ -127,6 +127,18 @@ typedef struct {
   int32_t candidate_status; /* value the launch callback returned, 0 = launched     */
 } r3_eval_result;
 
+/* Accumulated stage times of r3_eval_candidate while profiling is on (host memory).
+ * Each stage is bracketed by HIP events on the caller's stream, so a stage time is the
+ * device time of its kernels plus their dispatch gaps. */
+typedef struct {
+  double restore_ms;   /* batched restore launches                         */
+  double candidate_ms; /* the launch callback's kernels                    */
+  double validate_ms;  /* fused compare+checksum launches and their finalize */
+  uint64_t restore_launches;
+  uint64_t candidate_launches;
+  uint64_t validate_launches;
+} r3_profile;
+
 /* The candidate: enqueue the kernel(s) under test on `stream`, operating in
  * place on the arena at d_live.  Must not synchronise.  Non-zero = failure. */
 typedef int (*r3_launch_fn)(void* user, void* d_live, void* stream);
@@ -146,6 +158,12 @@ const char* r3_strerror(int status);
  * a small pinned staging buffer).  R3_EHIP if the device cannot be used. */
 int r3_ctx_create(r3_ctx** out, int device);
 int r3_ctx_destroy(r3_ctx* ctx);
+
+/* Stage profiling of r3_eval_candidate (off by default; costs two extra events per
+ * replay).  r3_ctx_profile_read copies the totals since the last reset into *out (host)
+ * and clears them when reset != 0. */
+int r3_ctx_profile(r3_ctx* ctx, int enable);
+int r3_ctx_profile_read(r3_ctx* ctx, r3_profile* out, int reset);
 
 /* Message of the last failing call on ctx ("" if none); valid until the next call. */
 const char* r3_last_error(const r3_ctx* ctx);

@@ -40,10 +40,17 @@ class EvalResult(ctypes.Structure):
                 ("ms_max", ctypes.c_float), ("candidate_status", ctypes.c_int32)]
 
 
+class Profile(ctypes.Structure):
+    _fields_ = [("restore_ms", ctypes.c_double), ("candidate_ms", ctypes.c_double),
+                ("validate_ms", ctypes.c_double), ("restore_launches", ctypes.c_uint64),
+                ("candidate_launches", ctypes.c_uint64), ("validate_launches", ctypes.c_uint64)]
+
+
 LAUNCH_FN = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p)
 
 DECLARED = [
     "r3_version", "r3_strerror", "r3_ctx_create", "r3_ctx_destroy", "r3_last_error",
+    "r3_ctx_profile", "r3_ctx_profile_read",
     "r3_table_validate", "r3_table_workspace_bytes", "r3_table_workspace_bytes_exact",
     "r3_tune_tiles", "r3_table_create", "r3_table_destroy", "r3_table_info", "r3_restore",
     "r3_checksum", "r3_compare", "r3_dirty_diff", "r3_record", "r3_eval_candidate",
@@ -74,6 +81,8 @@ def lib():
         L.r3_ctx_create.argtypes = [ctypes.POINTER(vp), ci]
         L.r3_ctx_destroy.argtypes = [vp]
         L.r3_last_error.argtypes = [vp]
+        L.r3_ctx_profile.argtypes = [vp, ci]
+        L.r3_ctx_profile_read.argtypes = [vp, ctypes.POINTER(Profile), ci]
         L.r3_last_error.restype = ctypes.c_char_p
         L.r3_table_validate.argtypes = [vp, u32, u64]
         L.r3_table_workspace_bytes.argtypes = [u32, u64]
@@ -179,6 +188,15 @@ class Context:
     def check(self, rc, what):
         if rc != OK:
             raise R3Error(rc, "%s: %s" % (what, self.last_error()))
+
+    def profile(self, enable):
+        self.check(lib().r3_ctx_profile(self.handle, int(bool(enable))), "r3_ctx_profile")
+
+    def profile_read(self, reset=True):
+        p = Profile()
+        self.check(lib().r3_ctx_profile_read(self.handle, ctypes.byref(p), int(bool(reset))),
+                   "r3_ctx_profile_read")
+        return p
 
     def close(self):
         if self.handle:

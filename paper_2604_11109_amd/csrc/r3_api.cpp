@@ -94,6 +94,19 @@ int r3_ctx_destroy(r3_ctx* ctx) {
   return R3_OK;
 }
 
+int r3_ctx_profile(r3_ctx* ctx, int enable) {
+  if (ctx == nullptr) return R3_EINVAL;
+  ctx->profiling = enable != 0;
+  return R3_OK;
+}
+
+int r3_ctx_profile_read(r3_ctx* ctx, r3_profile* out, int reset) {
+  if (ctx == nullptr || out == nullptr) return R3_EINVAL;
+  *out = ctx->profile;
+  if (reset) ctx->profile = r3_profile{};
+  return R3_OK;
+}
+
 const char* r3_last_error(const r3_ctx* ctx) { return ctx ? ctx->err.c_str() : "context is NULL"; }
 
 int r3_table_create(r3_ctx* ctx, const r3_region* host_tbl, uint32_t n, uint64_t arena_bytes,
@@ -269,7 +282,10 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
 
   DeviceGuard guard(ctx->device);
   hipStream_t s = as_stream(stream);
-  while (ctx->events.size() < 2 * total) {
+  // Events of replay r: [4r] before the restore and [4r+3] after the validation (only when
+  // profiling), [4r+1] / [4r+2] around the candidate.
+  const bool prof = ctx->profiling;
+  while (ctx->events.size() < 4 * total) {
     hipEvent_t ev;
     hipError_t e = hipEventCreate(&ev);
     if (e != hipSuccess) return fail_hip(ctx, e, "event create");
@@ -284,17 +300,26 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
   int cand = 0;
   hipError_t e = hipSuccess;
   uint32_t done = 0;
+  std::vector<uint8_t> validated(total, 0);
   for (uint32_t rep = 0; rep < total; ++rep) {
+    if (prof) {
+      e = hipEventRecord(ctx->events[4 * rep], s);
+      if (e != hipSuccess) break;
+    }
     e = r3::launch_restore(restore_tbl->dev, d_prologue, d_live, s);
     if (e != hipSuccess) break;
-    if (launch) {
-      e = hipEventRecord(ctx->events[2 * rep], s);
+    if (launch || prof) {
+      e = hipEventRecord(ctx->events[4 * rep + 1], s);
       if (e != hipSuccess) break;
+    }
+    if (launch) {
       cand = launch(user, d_live, stream);
       hipError_t le = hipGetLastError();
       if (cand == 0 && le != hipSuccess) cand = -(int)le;
       if (cand != 0) break;
-      e = hipEventRecord(ctx->events[2 * rep + 1], s);
+    }
+    if (launch || prof) {
+      e = hipEventRecord(ctx->events[4 * rep + 2], s);
       if (e != hipSuccess) break;
     }
     const bool validate = compare_policy == R3_POLICY_EVERY ||
@@ -305,6 +330,11 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
                              &check_tbl->dev.summaries[n_validated], s);
       if (e != hipSuccess) break;
       ++n_validated;
+      validated[rep] = 1;
+      if (prof) {
+        e = hipEventRecord(ctx->events[4 * rep + 3], s);
+        if (e != hipSuccess) break;
+      }
     }
     ++done;
   }
@@ -332,7 +362,7 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
     std::vector<float> ms;
     for (uint32_t rep = warmup; rep < done; ++rep) {
       float t = 0.f;
-      if (hipEventElapsedTime(&t, ctx->events[2 * rep], ctx->events[2 * rep + 1]) == hipSuccess)
+      if (hipEventElapsedTime(&t, ctx->events[4 * rep + 1], ctx->events[4 * rep + 2]) == hipSuccess)
         ms.push_back(t);
     }
     if (!ms.empty()) {
@@ -341,6 +371,25 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
       host_out->ms_max = ms.back();
       host_out->ms_median = ms.size() % 2 ? ms[ms.size() / 2]
                                           : 0.5f * (ms[ms.size() / 2 - 1] + ms[ms.size() / 2]);
+    }
+  }
+  if (prof) {
+    for (uint32_t rep = 0; rep < done; ++rep) {
+      float t = 0.f;
+      if (hipEventElapsedTime(&t, ctx->events[4 * rep], ctx->events[4 * rep + 1]) == hipSuccess) {
+        ctx->profile.restore_ms += t;
+        ctx->profile.restore_launches += 1;
+      }
+      if (launch &&
+          hipEventElapsedTime(&t, ctx->events[4 * rep + 1], ctx->events[4 * rep + 2]) == hipSuccess) {
+        ctx->profile.candidate_ms += t;
+        ctx->profile.candidate_launches += 1;
+      }
+      if (validated[rep] &&
+          hipEventElapsedTime(&t, ctx->events[4 * rep + 2], ctx->events[4 * rep + 3]) == hipSuccess) {
+        ctx->profile.validate_ms += t;
+        ctx->profile.validate_launches += 1;
+      }
     }
   }
   if (cand != 0) return fail(ctx, R3_ECANDIDATE, "the candidate failed to launch");

@@ -103,7 +103,9 @@ struct r3_ctx {
   int device = 0;
   std::string err;
   r3_summary* pinned = nullptr;  // R3_MAX_REPLAYS summaries, pinned host memory
-  std::vector<hipEvent_t> events;  // 2 per replay, grown on demand
+  std::vector<hipEvent_t> events;  // 4 per replay, grown on demand
+  bool profiling = false;
+  r3_profile profile{};
 };
 
 struct r3_table {
