@@ -37,6 +37,9 @@ def parse():
                    choices=["jacobi", "replay_small", "many_regions", "large_snapshot", "spmv"])
     p.add_argument("--no-large", action="store_true", help="skip the extra large-snapshot leg")
     p.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    p.add_argument("--calibrate-copy", action="store_true",
+                   help="also run 5 plain copies of 1 GiB (plain_copy_kernel), the yardstick for "
+                        "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
     return p.parse_args()
 
 
@@ -252,6 +255,15 @@ def main():
                 "large_snapshot": (5, 1), "spmv": (128, 8)}
     steps = a.steps if a.steps is not None else defaults[a.workload][0]
     warmup = a.warmup if a.warmup is not None else defaults[a.workload][1]
+
+    if a.calibrate_copy:
+        buf = torch.zeros(2 << 30, dtype=torch.uint8, device="cuda:0")
+        buf[:1 << 30].fill_(7)
+        for _ in range(5):
+            wl.plain_copy(buf, 0, 1 << 30, 1 << 30)
+        torch.cuda.synchronize()
+        del buf
+        torch.cuda.empty_cache()
 
     rp = Replay(a.workload, r3, wl, ctx, torch)
     dt, prof = timed_run(rp, steps, warmup)

@@ -77,7 +77,12 @@ int r3_ctx_create(r3_ctx** out, int device) {
   DeviceGuard guard(device);
   if (!guard.ok ||
       hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned), R3_MAX_REPLAYS * sizeof(r3_summary),
-                    hipHostMallocDefault) != hipSuccess) {
+                    hipHostMallocMapped) != hipSuccess) {
+    delete ctx;
+    return R3_EHIP;
+  }
+  if (hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->pinned_dev), ctx->pinned, 0) != hipSuccess) {
+    (void)hipHostFree(ctx->pinned);
     delete ctx;
     return R3_EHIP;
   }
@@ -153,6 +158,7 @@ int r3_table_create(r3_ctx* ctx, const r3_region* host_tbl, uint32_t n, uint64_t
   tbl->dev.min_shift = plan.min_shift;
   tbl->dev.cap_log2 = plan.cap_log2;
   tbl->dev.max_region_tiles = plan.max_region_tiles;
+  tbl->dev.max_shift = plan.max_shift;
   tbl->dev.n_tiles = plan.tiles.size();
   *out = tbl;
   return R3_OK;
@@ -207,7 +213,8 @@ int r3_compare(r3_ctx* ctx, const r3_table* tbl, const void* d_live, const void*
     return fail(ctx, R3_EINVAL, "pointer is NULL");
   if (!aligned16(d_live) || !aligned16(d_golden)) return fail(ctx, R3_EALIGN, "arena base not 16-byte aligned");
   DeviceGuard guard(ctx->device);
-  hipError_t e = r3::launch_compare(tbl->dev, d_live, d_golden, d_out, d_summary, as_stream(stream));
+  hipError_t e = r3::launch_compare(tbl->dev, d_live, d_golden, d_out, d_summary, nullptr,
+                                    as_stream(stream));
   return e == hipSuccess ? R3_OK : fail_hip(ctx, e, "compare launch");
 }
 
@@ -326,8 +333,8 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
                           (compare_policy == R3_POLICY_FIRST && rep == 0) ||
                           (compare_policy == R3_POLICY_LAST && rep == total - 1);
     if (validate) {
-      e = r3::launch_compare(check_tbl->dev, d_live, d_epilogue, d_regions,
-                             &check_tbl->dev.summaries[n_validated], s);
+      e = r3::launch_compare(check_tbl->dev, d_live, d_epilogue, d_regions, nullptr,
+                             &ctx->pinned_dev[n_validated], s);
       if (e != hipSuccess) break;
       ++n_validated;
       validated[rep] = 1;
@@ -338,9 +345,6 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
     }
     ++done;
   }
-  if (e == hipSuccess && n_validated)
-    e = hipMemcpyAsync(ctx->pinned, check_tbl->dev.summaries, n_validated * sizeof(r3_summary),
-                       hipMemcpyDeviceToHost, s);
   hipError_t we = hipStreamSynchronize(s);
   if (e == hipSuccess) e = we;
   if (e != hipSuccess) return fail_hip(ctx, e, "replay loop");

@@ -60,12 +60,13 @@ struct TableDev {
   uint32_t min_shift;         // log2 of the smallest tile
   uint32_t cap_log2;          // log2 of the most tiles a region may have
   uint32_t max_region_tiles;  // largest tile count of any region (sizes the finalize block)
+  uint32_t max_shift;         // log2 of the largest tile of any region
   uint64_t n_tiles;
 };
 
 // Host-side plan of a table: how the regions split into tiles.
 struct TablePlan {
-  uint32_t min_shift = 0, cap_log2 = 0, max_region_tiles = 0;
+  uint32_t min_shift = 0, cap_log2 = 0, max_region_tiles = 0, max_shift = 0;
   uint64_t total_bytes = 0;
   std::vector<uint64_t> tile_begin;  // n + 1
   std::vector<Tile> tiles;
@@ -93,7 +94,8 @@ hipError_t launch_restore(const TableDev& t, const void* src, void* dst, hipStre
 hipError_t launch_copy_flat(const void* src, void* dst, uint64_t bytes, hipStream_t s);
 hipError_t launch_checksum(const TableDev& t, const void* arena, uint64_t* out, hipStream_t s);
 hipError_t launch_compare(const TableDev& t, const void* live, const void* golden,
-                          r3_region_result* out, r3_summary* summary, hipStream_t s);
+                          r3_region_result* out, r3_summary* summary, r3_summary* host_summary,
+                          hipStream_t s);
 hipError_t launch_dirty_diff(const void* pre, const void* post, uint64_t bytes, uint32_t page_bytes,
                              uint64_t* bitmap, uint64_t* dirty_count, hipStream_t s);
 
@@ -102,7 +104,8 @@ hipError_t launch_dirty_diff(const void* pre, const void* post, uint64_t bytes, 
 struct r3_ctx {
   int device = 0;
   std::string err;
-  r3_summary* pinned = nullptr;  // R3_MAX_REPLAYS summaries, pinned host memory
+  r3_summary* pinned = nullptr;      // R3_MAX_REPLAYS summaries, pinned host memory
+  r3_summary* pinned_dev = nullptr;  // the same memory as the device addresses it
   std::vector<hipEvent_t> events;  // 4 per replay, grown on demand
   bool profiling = false;
   r3_profile profile{};

@@ -92,6 +92,7 @@ void plan_table(const r3_region* t, uint32_t n, TablePlan* plan) {
   plan->cap_log2 = tu.cap_log2;
   plan->total_bytes = 0;
   plan->max_region_tiles = 0;
+  plan->max_shift = tu.min_shift;
   plan->tile_begin.assign((size_t)n + 1, 0);
   uint64_t count = 0;
   for (uint32_t i = 0; i < n; ++i) {
@@ -99,6 +100,7 @@ void plan_table(const r3_region* t, uint32_t n, TablePlan* plan) {
     uint32_t s = tile_shift(t[i].bytes, tu.min_shift, tu.cap_log2);
     uint64_t k = (t[i].bytes + ((1ull << s) - 1)) >> s;
     if (k > plan->max_region_tiles) plan->max_region_tiles = (uint32_t)k;
+    if (k && s > plan->max_shift) plan->max_shift = s;
     count += k;
     plan->total_bytes += t[i].bytes;
   }

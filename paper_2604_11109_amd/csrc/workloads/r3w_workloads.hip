@@ -27,7 +27,14 @@ typedef struct {
   uint32_t rows, rows_per_wave, block, reserved;
 } r3w_spmv_args;
 
+// A plain grid-stride copy of `bytes` (multiple of 16) from src_off to dst_off inside the
+// arena: the yardstick that hardware traffic counters are scaled against.
+typedef struct {
+  uint64_t src_off, dst_off, bytes;
+} r3w_copy_args;
+
 int r3w_jacobi_launch(void* user, void* d_live, void* stream);
+int r3w_copy_launch(void* user, void* d_live, void* stream);
 int r3w_spmv_launch(void* user, void* d_live, void* stream);
 int r3w_failing_launch(void* user, void* d_live, void* stream);
 }
@@ -54,6 +61,11 @@ __global__ void jacobi_kernel(const double* __restrict__ in, double* __restrict_
     s = s + in[idx + n2];
     out[idx] = s * (1.0 / 7.0);
   }
+}
+
+__global__ void plain_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, uint64_t n) {
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
 template <int LANES>  // lanes that share one row
@@ -118,6 +130,19 @@ int r3w_jacobi_launch(void* user, void* d_live, void* stream) {
     case 2: jacobi_kernel<2><<<grid, a->block, 0, s>>>(in, out, a->n, x_end, total, stride); break;
     default: jacobi_kernel<4><<<grid, a->block, 0, s>>>(in, out, a->n, x_end, total, stride); break;
   }
+  return hipGetLastError() == hipSuccess ? 0 : 5;
+}
+
+int r3w_copy_launch(void* user, void* d_live, void* stream) {
+  const r3w_copy_args* a = static_cast<const r3w_copy_args*>(user);
+  if (a == nullptr || d_live == nullptr) return 1;
+  if ((a->src_off | a->dst_off | a->bytes) & 15) return 2;
+  uint8_t* base = static_cast<uint8_t*>(d_live);
+  const uint64_t n = a->bytes / 16;
+  if (n == 0) return 0;
+  const uint32_t grid = (uint32_t)((n + 255) / 256 < 65536 ? (n + 255) / 256 : 65536);
+  plain_copy_kernel<<<grid, 256, 0, static_cast<hipStream_t>(stream)>>>(
+      reinterpret_cast<const uint4*>(base + a->src_off), reinterpret_cast<uint4*>(base + a->dst_off), n);
   return hipGetLastError() == hipSuccess ? 0 : 5;
 }
 

@@ -20,6 +20,10 @@ class SpmvArgs(ctypes.Structure):
                 ("block", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
+class CopyArgs(ctypes.Structure):
+    _fields_ = [("src_off", ctypes.c_uint64), ("dst_off", ctypes.c_uint64), ("bytes", ctypes.c_uint64)]
+
+
 def lib():
     global _lib
     if _lib is None:
@@ -41,6 +45,19 @@ def jacobi_launch():
 
 def spmv_launch():
     return _addr("r3w_spmv_launch")
+
+
+def copy_launch():
+    return _addr("r3w_copy_launch")
+
+
+def plain_copy(d_arena, src_off, dst_off, nbytes, stream=0):
+    """Run the plain copy kernel once inside d_arena (a uint8 CUDA tensor)."""
+    lib().r3w_copy_launch.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    args = CopyArgs(src_off, dst_off, nbytes)
+    rc = lib().r3w_copy_launch(ctypes.addressof(args), d_arena.data_ptr(), stream)
+    if rc:
+        raise RuntimeError("plain copy launch failed: %d" % rc)
 
 
 def failing_launch():
