@@ -189,6 +189,10 @@ size_t r3_table_workspace_bytes_exact(const r3_region* host_tbl, uint32_t n, uin
  * tiles one region is split into, a power of two 64 .. 65536.  0 = default (4 KiB, 8192). */
 int r3_tune_tiles(uint32_t min_tile_bytes, uint32_t max_tiles_per_region);
 
+/* Tuning hook (process-wide): bytes one wavefront moves in the copy kernels (a power of two,
+ * 1 KiB .. 1 MiB) and their threads per block (64, 128 or 256).  0 = default. */
+int r3_tune_copy(uint32_t bytes_per_wavefront, uint32_t block_threads);
+
 /* Validate host_tbl, split its regions into tiles, and upload regions and tile
  * list into the caller's workspace d_ws (device, 256-byte aligned, at least
  * r3_table_workspace_bytes).  Synchronous (uses blocking copies).  The table

@@ -52,7 +52,7 @@ DECLARED = [
     "r3_version", "r3_strerror", "r3_ctx_create", "r3_ctx_destroy", "r3_last_error",
     "r3_ctx_profile", "r3_ctx_profile_read",
     "r3_table_validate", "r3_table_workspace_bytes", "r3_table_workspace_bytes_exact",
-    "r3_tune_tiles", "r3_table_create", "r3_table_destroy", "r3_table_info", "r3_restore",
+    "r3_tune_tiles", "r3_tune_copy", "r3_table_create", "r3_table_destroy", "r3_table_info", "r3_restore",
     "r3_checksum", "r3_compare", "r3_dirty_diff", "r3_record", "r3_eval_candidate",
 ]
 
@@ -90,6 +90,7 @@ def lib():
         L.r3_table_workspace_bytes_exact.argtypes = [vp, u32, u64]
         L.r3_table_workspace_bytes_exact.restype = sz
         L.r3_tune_tiles.argtypes = [u32, u32]
+        L.r3_tune_copy.argtypes = [u32, u32]
         L.r3_table_create.argtypes = [vp, vp, u32, u64, vp, sz, ctypes.POINTER(vp)]
         L.r3_table_destroy.argtypes = [vp]
         L.r3_table_info.argtypes = [vp, ctypes.POINTER(u32), ctypes.POINTER(u64), ctypes.POINTER(u32),
@@ -147,6 +148,12 @@ def r3_tune_tiles(min_tile_bytes=0, max_tiles_per_region=0):
     rc = lib().r3_tune_tiles(min_tile_bytes, max_tiles_per_region)
     if rc != OK:
         raise R3Error(rc, "r3_tune_tiles")
+
+
+def r3_tune_copy(bytes_per_wavefront=0, block_threads=0):
+    rc = lib().r3_tune_copy(bytes_per_wavefront, block_threads)
+    if rc != OK:
+        raise R3Error(rc, "r3_tune_copy")
 
 
 def _ptr(t):

@@ -99,6 +99,18 @@ int r3_ctx_destroy(r3_ctx* ctx) {
   return R3_OK;
 }
 
+int r3_tune_copy(uint32_t bytes_per_wavefront, uint32_t block_threads) {
+  uint32_t shift = 0;
+  while ((1u << shift) < bytes_per_wavefront) ++shift;
+  if (bytes_per_wavefront == 0) shift = 10;
+  if (block_threads == 0) block_threads = 64;
+  if ((1u << shift) != (bytes_per_wavefront ? bytes_per_wavefront : 1024u) || shift < 10 || shift > 20)
+    return R3_EINVAL;
+  if (block_threads != 64 && block_threads != 128 && block_threads != 256) return R3_EINVAL;
+  r3::set_copy_shape(shift, block_threads);
+  return R3_OK;
+}
+
 int r3_ctx_profile(r3_ctx* ctx, int enable) {
   if (ctx == nullptr) return R3_EINVAL;
   ctx->profiling = enable != 0;

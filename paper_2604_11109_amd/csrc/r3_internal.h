@@ -90,6 +90,7 @@ int validate_table(const r3_region* t, uint32_t n, uint64_t arena_bytes);
 void plan_table(const r3_region* t, uint32_t n, TablePlan* plan);
 
 // Kernel launchers (r3_kernels.hip).  All enqueue on `s` and return the launch status.
+void set_copy_shape(uint32_t shift, uint32_t block);
 hipError_t launch_restore(const TableDev& t, const void* src, void* dst, hipStream_t s);
 hipError_t launch_copy_flat(const void* src, void* dst, uint64_t bytes, hipStream_t s);
 hipError_t launch_checksum(const TableDev& t, const void* arena, uint64_t* out, hipStream_t s);

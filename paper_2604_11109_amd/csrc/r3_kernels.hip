@@ -190,35 +190,36 @@ __device__ __forceinline__ uint32_t elem_size_dev(uint32_t dtype) {
   return dtype == R3_U8 ? 1u : dtype == R3_BF16 ? 2u : dtype == R3_F64 ? 8u : 4u;
 }
 
-// Copy kernels run best here as many short wavefronts that each move 4 KiB (four 16-byte
-// loads and stores per lane, no loop) in address order: measured 6.1 TB/s against 5.1-5.4
-// TB/s for wavefronts that walk 64 KiB or more.  A table tile larger than 4 KiB is therefore
-// spread over 2^sub_log2 consecutive wavefronts; slots past the end of a tile exit at once.
-constexpr uint32_t kCopyShift = 12;
-
-__global__ __launch_bounds__(kBlock) void restore_kernel(TableDev t, const uint8_t* src,
-                                                         uint8_t* dst, uint32_t sub_log2) {
-  const uint64_t slot = (uint64_t)blockIdx.x * kWavesPerBlock + wave_in_block();
+// Copy kernels run best here as very many short wavefronts that each move 1 KiB (one
+// 16-byte load and store per lane, no loop) in address order: measured 6.6 TB/s against
+// 5.1-5.4 TB/s for wavefronts that walk 64 KiB or more.  A table tile is therefore spread
+// over 2^sub_log2 consecutive wavefront slots; slots past the end of a tile exit at once.
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void restore_kernel(TableDev t, const uint8_t* src, uint8_t* dst,
+                                                        uint32_t sub_log2, uint32_t copy_shift) {
+  const uint64_t slot = (uint64_t)blockIdx.x * (BLOCK / 64) + wave_in_block();
   const uint64_t tile_id = slot >> sub_log2;
   if (tile_id >= t.n_tiles) return;
   const uint32_t sub = (uint32_t)(slot & ((1ull << sub_log2) - 1));
   const TileView tv = resolve_tile(t, tile_id);
-  const uint64_t begin = (uint64_t)sub << kCopyShift;
+  const uint64_t begin = (uint64_t)sub << copy_shift;
   if (begin >= tv.len) return;
   const uint32_t left = tv.len - (uint32_t)begin;
-  const uint32_t len = left < (1u << kCopyShift) ? left : (1u << kCopyShift);
+  const uint32_t len = left < (1u << copy_shift) ? left : (1u << copy_shift);
   const uint64_t at = tv.offset + tv.rel_start + begin;
   copy_span(src + at, dst + at, len, elem_size_dev(tv.dtype), lane_id());
 }
 
-// Whole-range copy for r3_record: wavefront k moves bytes [4096 k, 4096 k + 4096).
-__global__ __launch_bounds__(kBlock) void copy_flat_kernel(const uint8_t* src, uint8_t* dst,
-                                                           uint64_t bytes, uint64_t n_slots) {
-  const uint64_t slot = (uint64_t)blockIdx.x * kWavesPerBlock + wave_in_block();
+// Whole-range copy for r3_record: wavefront k moves bytes [k << copy_shift, (k+1) << copy_shift).
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void copy_flat_kernel(const uint8_t* src, uint8_t* dst,
+                                                          uint64_t bytes, uint64_t n_slots,
+                                                          uint32_t copy_shift) {
+  const uint64_t slot = (uint64_t)blockIdx.x * (BLOCK / 64) + wave_in_block();
   if (slot >= n_slots) return;
-  const uint64_t at = slot << kCopyShift;
+  const uint64_t at = slot << copy_shift;
   const uint64_t left = bytes - at;
-  const uint32_t len = (uint32_t)(left < (1ull << kCopyShift) ? left : (1ull << kCopyShift));
+  const uint32_t len = (uint32_t)(left < (1ull << copy_shift) ? left : (1ull << copy_shift));
   copy_span(src + at, dst + at, len, 1, lane_id());
 }
 
@@ -784,22 +785,47 @@ uint32_t grid_for(uint64_t tiles) { return (uint32_t)((tiles + kWavesPerBlock - 
 
 }  // namespace
 
+// Bytes one wavefront copies (log2) and threads per block of the copy kernels.  Measured on
+// MI355X (restore of 2 x 128 MiB / 4 x 2 GiB): 1 KiB per wavefront in 64-thread blocks 6.6
+// TB/s, 4 KiB in 256-thread blocks 6.2 / 5.8 TB/s, 8 KiB 6.1 / 5.3 TB/s.
+static uint32_t g_copy_shift = 10;
+static uint32_t g_copy_block = 64;
+
+void set_copy_shape(uint32_t shift, uint32_t block) {
+  g_copy_shift = shift;
+  g_copy_block = block;
+}
+
 hipError_t launch_restore(const TableDev& t, const void* src, void* dst, hipStream_t s) {
   if (t.n_tiles == 0) return hipSuccess;
-  const uint32_t sub_log2 = t.max_shift > kCopyShift ? t.max_shift - kCopyShift : 0;
+  const uint32_t cs = g_copy_shift, wpb = g_copy_block / 64;
+  const uint32_t sub_log2 = t.max_shift > cs ? t.max_shift - cs : 0;
   const uint64_t slots = t.n_tiles << sub_log2;
-  const uint64_t blocks = (slots + kWavesPerBlock - 1) / kWavesPerBlock;
+  const uint64_t blocks = (slots + wpb - 1) / wpb;
   if (blocks > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
-  restore_kernel<<<(uint32_t)blocks, kBlock, 0, s>>>(t, (const uint8_t*)src, (uint8_t*)dst, sub_log2);
+  const uint8_t* a = (const uint8_t*)src;
+  uint8_t* b = (uint8_t*)dst;
+  switch (g_copy_block) {
+    case 64: restore_kernel<64><<<(uint32_t)blocks, 64, 0, s>>>(t, a, b, sub_log2, cs); break;
+    case 128: restore_kernel<128><<<(uint32_t)blocks, 128, 0, s>>>(t, a, b, sub_log2, cs); break;
+    default: restore_kernel<256><<<(uint32_t)blocks, 256, 0, s>>>(t, a, b, sub_log2, cs); break;
+  }
   return hipGetLastError();
 }
 
 hipError_t launch_copy_flat(const void* src, void* dst, uint64_t bytes, hipStream_t s) {
   if (bytes == 0) return hipSuccess;
-  const uint64_t n_slots = (bytes + ((1ull << kCopyShift) - 1)) >> kCopyShift;
-  const uint64_t blocks = (n_slots + kWavesPerBlock - 1) / kWavesPerBlock;
+  const uint32_t cs = g_copy_shift, wpb = g_copy_block / 64;
+  const uint64_t n_slots = (bytes + ((1ull << cs) - 1)) >> cs;
+  const uint64_t blocks = (n_slots + wpb - 1) / wpb;
   if (blocks > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
-  copy_flat_kernel<<<(uint32_t)blocks, kBlock, 0, s>>>((const uint8_t*)src, (uint8_t*)dst, bytes, n_slots);
+  const uint8_t* a = (const uint8_t*)src;
+  uint8_t* b = (uint8_t*)dst;
+  switch (g_copy_block) {
+    case 64: copy_flat_kernel<64><<<(uint32_t)blocks, 64, 0, s>>>(a, b, bytes, n_slots, cs); break;
+    case 128: copy_flat_kernel<128><<<(uint32_t)blocks, 128, 0, s>>>(a, b, bytes, n_slots, cs); break;
+    default: copy_flat_kernel<256><<<(uint32_t)blocks, 256, 0, s>>>(a, b, bytes, n_slots, cs); break;
+  }
   return hipGetLastError();
 }
 
