@@ -144,8 +144,7 @@ int r3_table_create(r3_ctx* ctx, const r3_region* host_tbl, uint32_t n, uint64_t
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return fail(ctx, R3_EHIP, "cannot select the device");
   uint8_t* ws = static_cast<uint8_t*>(d_ws);
-  hipError_t e = hipMemset(ws + lay.ticket, 0, 256);
-  if (e == hipSuccess) e = hipMemcpy(ws + lay.regions, host_tbl, (size_t)n * sizeof(r3_region), hipMemcpyHostToDevice);
+  hipError_t e = hipMemcpy(ws + lay.regions, host_tbl, (size_t)n * sizeof(r3_region), hipMemcpyHostToDevice);
   if (e == hipSuccess)
     e = hipMemcpy(ws + lay.tile_begin, plan.tile_begin.data(), plan.tile_begin.size() * sizeof(uint64_t),
                   hipMemcpyHostToDevice);
@@ -160,12 +159,10 @@ int r3_table_create(r3_ctx* ctx, const r3_region* host_tbl, uint32_t n, uint64_t
   tbl->ctx = ctx;
   tbl->arena_bytes = arena_bytes;
   tbl->total_bytes = plan.total_bytes;
-  tbl->dev.ticket = reinterpret_cast<uint32_t*>(ws + lay.ticket);
   tbl->dev.regions = reinterpret_cast<const r3_region*>(ws + lay.regions);
   tbl->dev.tile_begin = reinterpret_cast<const uint64_t*>(ws + lay.tile_begin);
   tbl->dev.tiles = reinterpret_cast<const r3::Tile*>(ws + lay.tiles);
   tbl->dev.partials = reinterpret_cast<r3::Partial*>(ws + lay.partials);
-  tbl->dev.summaries = reinterpret_cast<r3_summary*>(ws + lay.summaries);
   tbl->dev.n_regions = n;
   tbl->dev.min_shift = plan.min_shift;
   tbl->dev.cap_log2 = plan.cap_log2;

@@ -50,12 +50,10 @@ static_assert(sizeof(r3_summary) == 40 && sizeof(r3_eval_result) == 56, "ABI lay
 
 // Device-side view of a table's workspace.
 struct TableDev {
-  uint32_t* ticket;           // finalize blocks done so far in the call in flight
   const r3_region* regions;   // n
   const uint64_t* tile_begin; // n + 1, prefix sum of tiles per region
   const Tile* tiles;          // n_tiles
   Partial* partials;          // n_tiles (checksum-only calls use the first 8 bytes * n_tiles)
-  r3_summary* summaries;      // R3_MAX_REPLAYS slots for r3_eval_candidate
   uint32_t n_regions;
   uint32_t min_shift;         // log2 of the smallest tile
   uint32_t cap_log2;          // log2 of the most tiles a region may have
@@ -73,7 +71,7 @@ struct TablePlan {
 };
 
 struct WorkspaceLayout {
-  size_t ticket, regions, tile_begin, tiles, partials, summaries, total;
+  size_t regions, tile_begin, tiles, partials, total;
 };
 
 struct Tuning {

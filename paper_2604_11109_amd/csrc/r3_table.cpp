@@ -49,12 +49,10 @@ static size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 WorkspaceLayout workspace_layout(uint32_t n, uint64_t tiles) {
   WorkspaceLayout w;
   size_t at = 0;
-  w.ticket = at;      at += 256;
   w.regions = at;     at += up256((size_t)n * sizeof(r3_region));
   w.tile_begin = at;  at += up256(((size_t)n + 1) * sizeof(uint64_t));
   w.tiles = at;       at += up256((size_t)tiles * sizeof(Tile));
   w.partials = at;    at += up256((size_t)tiles * sizeof(Partial));
-  w.summaries = at;   at += up256((size_t)R3_MAX_REPLAYS * sizeof(r3_summary));
   w.total = at;
   return w;
 }
