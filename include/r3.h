@@ -159,10 +159,11 @@ const char* r3_strerror(int status);
 int r3_ctx_create(r3_ctx** out, int device);
 int r3_ctx_destroy(r3_ctx* ctx);
 
-/* Stage profiling of r3_eval_candidate (off by default; costs two extra events per
- * replay).  r3_ctx_profile_read copies the totals since the last reset into *out (host)
- * and clears them when reset != 0. */
-int r3_ctx_profile(r3_ctx* ctx, int enable);
+/* Stage profiling of r3_eval_candidate: period 0 = off (default), n > 0 = bracket the stages
+ * of every n-th evaluation with events (two extra events per replay of that evaluation).
+ * r3_ctx_profile_read copies the totals since the last reset into *out (host) and clears
+ * them when reset != 0. */
+int r3_ctx_profile(r3_ctx* ctx, int period);
 int r3_ctx_profile_read(r3_ctx* ctx, r3_profile* out, int reset);
 
 /* Message of the last failing call on ctx ("" if none); valid until the next call. */

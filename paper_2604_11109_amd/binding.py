@@ -196,8 +196,9 @@ class Context:
         if rc != OK:
             raise R3Error(rc, "%s: %s" % (what, self.last_error()))
 
-    def profile(self, enable):
-        self.check(lib().r3_ctx_profile(self.handle, int(bool(enable))), "r3_ctx_profile")
+    def profile(self, period):
+        """0 = off, n = stage events on every n-th evaluation."""
+        self.check(lib().r3_ctx_profile(self.handle, int(period)), "r3_ctx_profile")
 
     def profile_read(self, reset=True):
         p = Profile()

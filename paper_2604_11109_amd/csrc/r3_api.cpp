@@ -76,7 +76,7 @@ int r3_ctx_create(r3_ctx** out, int device) {
   ctx->device = device;
   DeviceGuard guard(device);
   if (!guard.ok ||
-      hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned), R3_MAX_REPLAYS * sizeof(r3_summary),
+      hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned), R3_MAX_REPLAYS * sizeof(r3::HostSlot),
                     hipHostMallocMapped) != hipSuccess) {
     delete ctx;
     return R3_EHIP;
@@ -111,9 +111,10 @@ int r3_tune_copy(uint32_t bytes_per_wavefront, uint32_t block_threads) {
   return R3_OK;
 }
 
-int r3_ctx_profile(r3_ctx* ctx, int enable) {
-  if (ctx == nullptr) return R3_EINVAL;
-  ctx->profiling = enable != 0;
+int r3_ctx_profile(r3_ctx* ctx, int period) {
+  if (ctx == nullptr || period < 0) return R3_EINVAL;
+  ctx->profile_period = (uint32_t)period;
+  ctx->evals = 0;
   return R3_OK;
 }
 
@@ -222,7 +223,7 @@ int r3_compare(r3_ctx* ctx, const r3_table* tbl, const void* d_live, const void*
     return fail(ctx, R3_EINVAL, "pointer is NULL");
   if (!aligned16(d_live) || !aligned16(d_golden)) return fail(ctx, R3_EALIGN, "arena base not 16-byte aligned");
   DeviceGuard guard(ctx->device);
-  hipError_t e = r3::launch_compare(tbl->dev, d_live, d_golden, d_out, d_summary, nullptr,
+  hipError_t e = r3::launch_compare(tbl->dev, d_live, d_golden, d_out, d_summary, nullptr, 0,
                                     as_stream(stream));
   return e == hipSuccess ? R3_OK : fail_hip(ctx, e, "compare launch");
 }
@@ -300,7 +301,7 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
   hipStream_t s = as_stream(stream);
   // Events of replay r: [4r] before the restore and [4r+3] after the validation (only when
   // profiling), [4r+1] / [4r+2] around the candidate.
-  const bool prof = ctx->profiling;
+  const bool prof = ctx->profile_period != 0 && (ctx->evals++ % ctx->profile_period) == 0;
   while (ctx->events.size() < 4 * total) {
     hipEvent_t ev;
     hipError_t e = hipEventCreate(&ev);
@@ -317,7 +318,9 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
   hipError_t e = hipSuccess;
   uint32_t done = 0;
   std::vector<uint8_t> validated(total, 0);
+  bool last_is_validation = false;  // the last work enqueued is a finalize pass that posts a seq
   for (uint32_t rep = 0; rep < total; ++rep) {
+    last_is_validation = false;
     if (prof) {
       e = hipEventRecord(ctx->events[4 * rep], s);
       if (e != hipSuccess) break;
@@ -343,7 +346,8 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
                           (compare_policy == R3_POLICY_LAST && rep == total - 1);
     if (validate) {
       e = r3::launch_compare(check_tbl->dev, d_live, d_epilogue, d_regions, nullptr,
-                             &ctx->pinned_dev[n_validated], s);
+                             &ctx->pinned_dev[n_validated], ++ctx->seq, s);
+      last_is_validation = true;
       if (e != hipSuccess) break;
       ++n_validated;
       validated[rep] = 1;
@@ -354,15 +358,29 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
     }
     ++done;
   }
-  hipError_t we = hipStreamSynchronize(s);
-  if (e == hipSuccess) e = we;
+  // Wait for the verdict.  When the last thing enqueued is a validation, its sequence number
+  // arriving in pinned memory says that everything before it on the stream has run; polling
+  // for it (bounded) avoids the wake-up latency of a stream wait.  Anything else, and any
+  // doubt, takes the stream wait.
+  bool arrived = false;
+  if (e == hipSuccess && cand == 0 && last_is_validation && n_validated) {
+    const volatile uint64_t* flag = &ctx->pinned[n_validated - 1].seq;
+    const uint64_t want = ctx->seq;
+    for (uint32_t spin = 0; spin < (1u << 22) && !arrived; ++spin)
+      arrived = __atomic_load_n(const_cast<const uint64_t*>(flag), __ATOMIC_ACQUIRE) == want;
+    if (arrived && prof) arrived = hipEventSynchronize(ctx->events[4 * (total - 1) + 3]) == hipSuccess;
+  }
+  if (!arrived) {
+    hipError_t we = hipStreamSynchronize(s);
+    if (e == hipSuccess) e = we;
+  }
   if (e != hipSuccess) return fail_hip(ctx, e, "replay loop");
 
   host_out->candidate_status = cand;
   for (uint32_t i = 0; i < n_validated; ++i)
-    host_out->total_mismatch = std::max(host_out->total_mismatch, ctx->pinned[i].total_mismatch);
+    host_out->total_mismatch = std::max(host_out->total_mismatch, ctx->pinned[i].summary.total_mismatch);
   if (n_validated) {
-    const r3_summary& last = ctx->pinned[n_validated - 1];
+    const r3_summary& last = ctx->pinned[n_validated - 1].summary;
     host_out->first_index = last.first_index;
     host_out->first_region = last.first_region;
     host_out->max_abs_err = last.max_abs_err;

@@ -62,6 +62,16 @@ struct TableDev {
   uint64_t n_tiles;
 };
 
+// One slot of the pinned host buffer that the replay loop hands to the finalize pass: the
+// table summary and, written after it with a system-scope release, the sequence number of
+// the validation that produced it (what the host polls for).
+struct HostSlot {
+  r3_summary summary;
+  uint64_t seq;
+  uint64_t pad[2];
+};
+static_assert(sizeof(HostSlot) == 64, "host slot layout");
+
 // Host-side plan of a table: how the regions split into tiles.
 struct TablePlan {
   uint32_t min_shift = 0, cap_log2 = 0, max_region_tiles = 0, max_shift = 0;
@@ -93,8 +103,8 @@ hipError_t launch_restore(const TableDev& t, const void* src, void* dst, hipStre
 hipError_t launch_copy_flat(const void* src, void* dst, uint64_t bytes, hipStream_t s);
 hipError_t launch_checksum(const TableDev& t, const void* arena, uint64_t* out, hipStream_t s);
 hipError_t launch_compare(const TableDev& t, const void* live, const void* golden,
-                          r3_region_result* out, r3_summary* summary, r3_summary* host_summary,
-                          hipStream_t s);
+                          r3_region_result* out, r3_summary* summary, HostSlot* host_slot,
+                          uint64_t host_seq, hipStream_t s);
 hipError_t launch_dirty_diff(const void* pre, const void* post, uint64_t bytes, uint32_t page_bytes,
                              uint64_t* bitmap, uint64_t* dirty_count, hipStream_t s);
 
@@ -103,10 +113,12 @@ hipError_t launch_dirty_diff(const void* pre, const void* post, uint64_t bytes, 
 struct r3_ctx {
   int device = 0;
   std::string err;
-  r3_summary* pinned = nullptr;      // R3_MAX_REPLAYS summaries, pinned host memory
-  r3_summary* pinned_dev = nullptr;  // the same memory as the device addresses it
+  r3::HostSlot* pinned = nullptr;      // R3_MAX_REPLAYS slots, pinned host memory
+  r3::HostSlot* pinned_dev = nullptr;  // the same memory as the device addresses it
+  uint64_t seq = 0;                    // sequence number of the last validation enqueued
+  uint32_t profile_period = 0;         // 0 = off, n = stage events on every n-th evaluation
+  uint64_t evals = 0;
   std::vector<hipEvent_t> events;  // 4 per replay, grown on demand
-  bool profiling = false;
   r3_profile profile{};
 };
 

@@ -729,11 +729,17 @@ __global__ __launch_bounds__(kBlock) void compare_kernel(TableDev t, const uint8
 }
 
 // One block per region folds that region's partials into its r3_region_result.  The table
-// summary goes to `summary` (device) and, when given, to `host_summary` (pinned host memory
-// mapped into the device's address space), which saves the caller a copy.
+// summary goes to `summary` (device) and, when given, to `host_slot` (pinned host memory
+// mapped into the device's address space) followed by its sequence number, which saves the
+// caller a copy and lets it poll for the verdict instead of waiting for the stream.
 struct Folded {
   uint64_t count, first, max_abs, max_rel, cks;
 };
+
+__device__ __forceinline__ void publish_seq(HostSlot* slot, uint64_t seq) {
+  __threadfence_system();  // the summary is in host memory before its sequence number
+  __hip_atomic_store(&slot->seq, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
 
 __device__ __forceinline__ void write_summary(r3_summary* dst, uint64_t total, uint32_t first_region,
                                               uint64_t first_index, uint64_t max_abs,
@@ -749,7 +755,7 @@ __device__ __forceinline__ void write_summary(r3_summary* dst, uint64_t total, u
 template <int BLOCK>
 __global__ __launch_bounds__(BLOCK) void compare_finalize_kernel(TableDev t, r3_region_result* out,
                                                                  r3_summary* summary,
-                                                                 r3_summary* host_summary) {
+                                                                 HostSlot* host_slot, uint64_t host_seq) {
   constexpr int NW = BLOCK / 64;
   constexpr int kAhead = 4;  // partials fetched per thread before any is folded
   __shared__ uint64_t sh[5][NW];
@@ -815,18 +821,21 @@ __global__ __launch_bounds__(BLOCK) void compare_finalize_kernel(TableDev t, r3_
   // summary_kernel, a separate launch: folding it in here through a "last block" ticket
   // needs a device-wide release fence per block, which cost 37 ns per region (150 us for
   // 4096 regions) when measured.
-  if (gridDim.x == 1 && tid == 0 && (summary != nullptr || host_summary != nullptr)) {
+  if (gridDim.x == 1 && tid == 0 && (summary != nullptr || host_slot != nullptr)) {
     const uint32_t fr = f.count ? 0u : R3_NO_REGION;
     const uint64_t fi = f.count ? f.first : R3_NO_INDEX;
     if (summary) write_summary(summary, f.count, fr, fi, f.max_abs, f.max_rel);
-    if (host_summary) write_summary(host_summary, f.count, fr, fi, f.max_abs, f.max_rel);
+    if (host_slot) {
+      write_summary(&host_slot->summary, f.count, fr, fi, f.max_abs, f.max_rel);
+      publish_seq(host_slot, host_seq);
+    }
   }
 }
 
 // Table verdict from the per-region results (one block; runs after the finalize launch).
 __global__ __launch_bounds__(kBlock) void summary_kernel(const r3_region_result* out, uint32_t n,
-                                                         r3_summary* summary,
-                                                         r3_summary* host_summary) {
+                                                         r3_summary* summary, HostSlot* host_slot,
+                                                         uint64_t host_seq) {
   __shared__ uint64_t sh[3][kWavesPerBlock];
   __shared__ uint32_t sh_first_region[kWavesPerBlock];
   const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -859,7 +868,10 @@ __global__ __launch_bounds__(kBlock) void summary_kernel(const r3_region_result*
     }
     const uint64_t first_index = first_region == R3_NO_REGION ? R3_NO_INDEX : out[first_region].first_mismatch;
     if (summary) write_summary(summary, total, first_region, first_index, max_abs, max_rel);
-    if (host_summary) write_summary(host_summary, total, first_region, first_index, max_abs, max_rel);
+    if (host_slot) {
+      write_summary(&host_slot->summary, total, first_region, first_index, max_abs, max_rel);
+      publish_seq(host_slot, host_seq);
+    }
   }
 }
 
@@ -999,8 +1011,8 @@ hipError_t launch_checksum(const TableDev& t, const void* arena, uint64_t* out, 
 }
 
 hipError_t launch_compare(const TableDev& t, const void* live, const void* golden,
-                          r3_region_result* out, r3_summary* summary, r3_summary* host_summary,
-                          hipStream_t s) {
+                          r3_region_result* out, r3_summary* summary, HostSlot* host_slot,
+                          uint64_t host_seq, hipStream_t s) {
   if (t.n_tiles) {
     compare_kernel<<<grid_for(t.n_tiles), kBlock, 0, s>>>(t, (const uint8_t*)live,
                                                           (const uint8_t*)golden);
@@ -1009,18 +1021,18 @@ hipError_t launch_compare(const TableDev& t, const void* live, const void* golde
   }
   switch (finalize_block(t.max_region_tiles)) {
     case 64:
-      compare_finalize_kernel<64><<<t.n_regions, 64, 0, s>>>(t, out, summary, host_summary);
+      compare_finalize_kernel<64><<<t.n_regions, 64, 0, s>>>(t, out, summary, host_slot, host_seq);
       break;
     case 256:
-      compare_finalize_kernel<256><<<t.n_regions, 256, 0, s>>>(t, out, summary, host_summary);
+      compare_finalize_kernel<256><<<t.n_regions, 256, 0, s>>>(t, out, summary, host_slot, host_seq);
       break;
     default:
-      compare_finalize_kernel<1024><<<t.n_regions, 1024, 0, s>>>(t, out, summary, host_summary);
+      compare_finalize_kernel<1024><<<t.n_regions, 1024, 0, s>>>(t, out, summary, host_slot, host_seq);
       break;
   }
   hipError_t e = hipGetLastError();
-  if (e == hipSuccess && t.n_regions > 1 && (summary != nullptr || host_summary != nullptr)) {
-    summary_kernel<<<1, kBlock, 0, s>>>(out, t.n_regions, summary, host_summary);
+  if (e == hipSuccess && t.n_regions > 1 && (summary != nullptr || host_slot != nullptr)) {
+    summary_kernel<<<1, kBlock, 0, s>>>(out, t.n_regions, summary, host_slot, host_seq);
     e = hipGetLastError();
   }
   return e;
