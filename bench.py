@@ -31,9 +31,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # each scaled by what the same counter reads for a plain 1 GiB copy (FETCH 2.0, WRITE 1.0).
 # Valid only for the kernel source they were taken with: reported as null otherwise.
 COUNTERS = {
-    "kernels_sha256_16": "5ed30506d982533e",
-    "jacobi": {"restore": 539004870, "validate": 269244523 + 339463},
-    "large_snapshot": {"restore": 68736504537, "validate": 68729134215 + 5345308},
+    "kernels_sha256_16": "9d28edf09dea4bbc",
+    "jacobi": {"restore": 538987720, "validate": 269139871 + 339367},
+    "large_snapshot": {"restore": 68737314671, "validate": 68728810857 + 5339092 + 6176},
 }
 
 
