@@ -75,6 +75,7 @@ class Replay:
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
         self.launch, self.candidates, self.expect_pass = None, [None], [None]
         self.host_case = None
+        self.baseline_index = 0
         if name == "jacobi":
             c = ri.jacobi(256)
             A = c["arena_bytes"]
@@ -129,12 +130,55 @@ class Replay:
             r3.r3_record(ctx, self.restore_tbl, self.d_live, self.launch, wl.spmv_args(c, 64, 256),
                          self.d_pro, self.d_epi)
             self.candidates = [wl.spmv_args(c, r, b) for r, b in ri.SPMV_VARIANTS]
+            self.baseline_index = ri.SPMV_VARIANTS.index((64, 256))
             self.expect_pass = [True if r >= 64 else None for r, _ in ri.SPMV_VARIANTS]
             self.desc = "CSR SpMV 2^21 rows x 27 nnz fp64, 64 launch configurations, full-arena restore 688 MiB"
         self.arena_bytes = A
         self.d_regions = torch.zeros(40 * self.check_tbl.n, dtype=torch.uint8, device="cuda:0")
         self.restore_bytes = 2 * self.restore_tbl.info()["total_bytes"]
         self.validate_bytes = 2 * self.check_tbl.info()["total_bytes"]
+
+    def enable_writeset(self, page=4096):
+        """Record once more with the dirty bitmap and build the write-set / guard tables."""
+        import numpy as np
+        r3, ctx, torch = self.r3, self.ctx, self.torch
+        A = self.arena_bytes
+        d_bm = torch.zeros(r3.bitmap_words(A, page), dtype=torch.int64, device="cuda:0")
+        self.d_live.copy_(self.d_pro)
+        r3.r3_record(ctx, self.restore_tbl, self.d_live, self.launch, self.candidates[self.baseline_index],
+                     self.d_pro, self.d_epi, page, d_bm)
+        bm = d_bm.cpu().numpy().view(np.uint64)
+        self.ws_tbl = r3.Table(ctx, r3.r3_writeset_regions(bm, A, page, 1), A)
+        self.guard_tbl = r3.Table(ctx, r3.r3_writeset_regions(bm, A, page, 0), A)
+        self.heal_tbl = r3.Table(ctx, [(0, A, 0, 0, 0.0, 0.0)], A)
+        self.d_expected = torch.zeros(self.guard_tbl.n, dtype=torch.int64, device="cuda:0")
+        self.d_scratch = torch.zeros(self.guard_tbl.n, dtype=torch.int64, device="cuda:0")
+        r3.r3_checksum(ctx, self.guard_tbl, self.d_pro, self.d_expected)
+        torch.cuda.synchronize()
+        self.d_live.copy_(self.d_pro)
+        return {"write_set_bytes": self.ws_tbl.info()["total_bytes"],
+                "guarded_bytes": self.guard_tbl.info()["total_bytes"]}
+
+    def step_writeset(self, i, guard_every=8):
+        """Restore only the recorded write-set; every guard_every-th evaluation also checks that
+        the rest of the state still carries its recorded checksums."""
+        k = i % len(self.candidates)
+        if i % guard_every == guard_every - 1:
+            rc, out, g = self.r3.r3_eval_candidate_guarded(
+                self.ctx, self.ws_tbl, self.d_pro, self.check_tbl, self.d_epi, self.d_live, self.launch,
+                self.candidates[k], 0, 1, self.r3.EVERY, self.d_regions, self.guard_tbl, self.d_expected,
+                self.d_scratch, every=0, heal_tbl=self.heal_tbl)
+            if g.failed_checks:
+                raise RuntimeError("guard failed for candidate %d" % k)
+        else:
+            rc, out = self.r3.r3_eval_candidate(self.ctx, self.ws_tbl, self.d_pro, self.check_tbl, self.d_epi,
+                                                self.d_live, self.launch, self.candidates[k], 0, 1,
+                                                self.r3.EVERY, self.d_regions)
+        want = self.expect_pass[k]
+        if rc != 0 or (want is not None and bool(out.passed) != want):
+            raise RuntimeError("write-set evaluation %d of %s gave pass=%d (expected %s), status %d"
+                               % (i, self.name, out.passed, want, rc))
+        return out
 
     def step(self, i):
         k = i % len(self.candidates)
@@ -163,6 +207,25 @@ def timed_run(rp, steps, warmup):
     prof = ctx.profile_read(reset=True)
     ctx.profile(0)
     return t1 - t0, prof
+
+
+def writeset_leg(rp, steps, warmup):
+    """The same workload with write-set driven restore and a periodic whole-state guard."""
+    info = rp.enable_writeset()
+    torch = rp.torch
+    for i in range(warmup):
+        rp.step_writeset(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        rp.step_writeset(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    info.update({"value": steps / dt, "unit": "evals/s", "ms_per_step": dt / steps * 1e3, "steps": steps,
+                 "guard_every": 8,
+                 "note": "restore covers only the pages the recorded kernel wrote; every 8th evaluation also "
+                         "checksums the rest of the arena against the recorded checksums"})
+    return info
 
 
 def stage_report(rp, prof):
@@ -301,6 +364,8 @@ def main():
     }
     cpu = None if a.no_cpu else cpu_baseline(rp)
     line["cpu_baseline"] = cpu
+    if a.workload in ("jacobi", "spmv"):
+        line["write_set_replay"] = writeset_leg(rp, steps, warmup)
     del rp
     torch.cuda.empty_cache()
     if a.workload != "large_snapshot" and not a.no_large:

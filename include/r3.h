@@ -139,6 +139,29 @@ typedef struct {
   uint64_t validate_launches;
 } r3_profile;
 
+/* Whole-state guard for replays that restore only a write-set (host memory).  The regions of
+ * guard_tbl are the part of the state the recorded kernel does NOT write; their checksums
+ * must stay what they were at record time, otherwise the candidate wrote outside its
+ * write-set and later replays would start from a wrong state. */
+typedef struct {
+  const struct r3_table* guard_tbl; /* table over the never-written part of the arena          */
+  const uint64_t* d_expected;       /* device: recorded checksums of its regions (n values)    */
+  uint64_t* d_scratch;              /* device: n values, overwritten by every check            */
+  const struct r3_table* heal_tbl;  /* optional: restored from the prologue if a check fails   */
+  uint32_t every;                   /* check after every `every`-th replay and after the last;
+                                       0 = only after the last                                 */
+  uint32_t reserved;
+} r3_guard;
+
+typedef struct {
+  uint32_t checks;          /* guard checks that ran                                        */
+  uint32_t failed_checks;   /* checks in which at least one region had changed              */
+  uint32_t changed_regions; /* most regions changed in any one check                        */
+  uint32_t first_region;    /* first changed region of the first failing check, R3_NO_REGION */
+  uint32_t healed;          /* 1 if heal_tbl was restored after a failure                   */
+  uint32_t reserved;
+} r3_guard_result;
+
 /* The candidate: enqueue the kernel(s) under test on `stream`, operating in
  * place on the arena at d_live.  Must not synchronise.  Non-zero = failure. */
 typedef int (*r3_launch_fn)(void* user, void* d_live, void* stream);
@@ -273,6 +296,29 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
                       r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
                       uint32_t compare_policy, r3_region_result* d_regions,
                       r3_eval_result* host_out, void* stream);
+
+/* ---- write-set driven replay ------------------------------------------- */
+
+/* Turn a page bitmap (host copy of what r3_dirty_diff / r3_record wrote) into regions:
+ * maximal runs of dirty pages (want_dirty != 0) or of clean pages (want_dirty == 0), as
+ * R3_U8 / R3_CMP_BITWISE regions in address order, the last one clipped to `bytes`.
+ * Writes at most cap regions to out (host; may be NULL when cap == 0) and the number of
+ * runs to *n_out; R3_ENOSPC if there are more runs than cap (then *n_out says how many). */
+int r3_writeset_regions(const uint64_t* host_bitmap, uint64_t bytes, uint32_t page_bytes,
+                        int want_dirty, r3_region* out, uint32_t cap, uint32_t* n_out);
+
+/* r3_eval_candidate with a restore table that covers only the recorded write-set, plus the
+ * guard above: after the replays selected by guard->every the checksums of guard_tbl's
+ * regions in live memory are compared, on the device, with guard->d_expected.  A failed check
+ * makes host_out->pass 0; if guard->heal_tbl is given it is then restored from d_prologue so
+ * that the next evaluation starts from the recorded state.  guard == NULL behaves exactly
+ * like r3_eval_candidate.  host_guard_out (host) may be NULL. */
+int r3_eval_candidate_guarded(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
+                              const r3_table* check_tbl, const void* d_epilogue, void* d_live,
+                              r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
+                              uint32_t compare_policy, r3_region_result* d_regions,
+                              r3_eval_result* host_out, const r3_guard* guard,
+                              r3_guard_result* host_guard_out, void* stream);
 
 #ifdef __cplusplus
 }

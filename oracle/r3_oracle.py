@@ -169,6 +169,24 @@ def dirty_diff(pre, post, page_bytes=4096):
     return bitmap, int(count.value)
 
 
+def writeset_regions(bitmap, nbytes, page_bytes, want_dirty):
+    """Maximal runs of dirty (or clean) pages of a write-set bitmap as byte regions
+    (offset, bytes, U8, BITWISE), the last one clipped to nbytes.  One page at a time."""
+    npages = -(-nbytes // page_bytes)
+    rows, start = [], None
+    for p in range(npages):
+        dirty = (int(bitmap[p // 64]) >> (p % 64)) & 1
+        want = bool(dirty) == bool(want_dirty)
+        if want and start is None:
+            start = p
+        elif not want and start is not None:
+            rows.append((start * page_bytes, p * page_bytes - start * page_bytes, U8, BITWISE, 0.0, 0.0))
+            start = None
+    if start is not None:
+        rows.append((start * page_bytes, nbytes - start * page_bytes, U8, BITWISE, 0.0, 0.0))
+    return make_table(rows)
+
+
 def record(tbl, live, launch, page_bytes=4096):
     """Section V-A: keep the state before and after one run of the recorded kernel.
 
@@ -185,7 +203,7 @@ def record(tbl, live, launch, page_bytes=4096):
 
 
 def eval_candidate(restore_tbl, prologue, check_tbl, epilogue, live, launch, warmup=0, reps=1,
-                   policy=EVERY):
+                   policy=EVERY, guard_tbl=None, guard_expected=None, guard_every=0, heal_tbl=None):
     """Sections V-B/V-C: for every replay restore, run, validate per `policy`.
 
     launch(live) mutates the arena in place and may return a non-zero status
@@ -197,6 +215,8 @@ def eval_candidate(restore_tbl, prologue, check_tbl, epilogue, live, launch, war
     if reps < 1 or total < 1:
         raise ValueError("reps")
     regions, last, worst, status = None, None, 0, 0
+    g_checks = g_failed = g_changed = 0
+    g_first = NO_REGION
     for rep in range(total):
         restore(restore_tbl, prologue, live)
         if launch is not None:
@@ -210,11 +230,27 @@ def eval_candidate(restore_tbl, prologue, check_tbl, epilogue, live, launch, war
             regions, s = compare(check_tbl, live, epilogue)
             last = s[0]
             worst = max(worst, int(last["total_mismatch"]))
-    out = {"candidate_status": status, "regions": regions, "total_mismatch": worst}
+        # whole-state guard: the part of the state the recorded kernel never writes must
+        # still carry its recorded checksums
+        if guard_tbl is not None and ((guard_every and (rep + 1) % guard_every == 0) or rep == total - 1):
+            changed = np.flatnonzero(checksum(guard_tbl, live) != np.asarray(guard_expected, dtype=np.uint64))
+            g_checks += 1
+            if changed.size:
+                if g_failed == 0:
+                    g_first = int(changed[0])
+                g_failed += 1
+                g_changed = max(g_changed, int(changed.size))
+    healed = 0
+    if g_failed and heal_tbl is not None:
+        restore(heal_tbl, prologue, live)
+        healed = 1
+    out = {"candidate_status": status, "regions": regions, "total_mismatch": worst,
+           "guard": {"checks": g_checks, "failed_checks": g_failed, "changed_regions": g_changed,
+                     "first_region": g_first, "healed": healed}}
     if last is not None:
         out.update(first_region=int(last["first_region"]), first_index=int(last["first_index"]),
                    max_abs_err=float(last["max_abs_err"]), max_rel_err=float(last["max_rel_err"]))
     else:
         out.update(first_region=NO_REGION, first_index=NO_INDEX, max_abs_err=0.0, max_rel_err=0.0)
-    out["pass"] = int(status == 0 and worst == 0)
+    out["pass"] = int(status == 0 and worst == 0 and g_failed == 0)
     return out

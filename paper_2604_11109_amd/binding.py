@@ -46,6 +46,18 @@ class Profile(ctypes.Structure):
                 ("candidate_launches", ctypes.c_uint64), ("validate_launches", ctypes.c_uint64)]
 
 
+class Guard(ctypes.Structure):
+    _fields_ = [("guard_tbl", ctypes.c_void_p), ("d_expected", ctypes.c_void_p),
+                ("d_scratch", ctypes.c_void_p), ("heal_tbl", ctypes.c_void_p),
+                ("every", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+
+
+class GuardResult(ctypes.Structure):
+    _fields_ = [("checks", ctypes.c_uint32), ("failed_checks", ctypes.c_uint32),
+                ("changed_regions", ctypes.c_uint32), ("first_region", ctypes.c_uint32),
+                ("healed", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+
+
 LAUNCH_FN = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p)
 
 DECLARED = [
@@ -54,6 +66,7 @@ DECLARED = [
     "r3_table_validate", "r3_table_workspace_bytes", "r3_table_workspace_bytes_exact",
     "r3_tune_tiles", "r3_tune_copy", "r3_table_create", "r3_table_destroy", "r3_table_info", "r3_restore",
     "r3_checksum", "r3_compare", "r3_dirty_diff", "r3_record", "r3_eval_candidate",
+    "r3_writeset_regions", "r3_eval_candidate_guarded",
 ]
 
 _lib = None
@@ -102,6 +115,10 @@ def lib():
         L.r3_record.argtypes = [vp, vp, vp, vp, vp, vp, vp, u32, vp, vp, vp, vp, vp]
         L.r3_eval_candidate.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, u32, vp,
                                         ctypes.POINTER(EvalResult), vp]
+        L.r3_writeset_regions.argtypes = [vp, u64, u32, ci, vp, u32, ctypes.POINTER(u32)]
+        L.r3_eval_candidate_guarded.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, u32, vp,
+                                                ctypes.POINTER(EvalResult), ctypes.POINTER(Guard),
+                                                ctypes.POINTER(GuardResult), vp]
         for name in DECLARED:
             getattr(L, name)  # AttributeError if the library does not export it
         _lib = L
@@ -350,6 +367,47 @@ def r3_eval_candidate(ctx, restore_tbl, d_prologue, check_tbl, d_epilogue, d_liv
         return rc, out
     ctx.check(rc, "r3_eval_candidate")
     return rc, out
+
+
+def r3_writeset_regions(host_bitmap, nbytes, page_bytes, want_dirty):
+    """host_bitmap: numpy uint64 array.  Returns a REGION_DTYPE array of the runs."""
+    bm = np.ascontiguousarray(host_bitmap, dtype=np.uint64)
+    n = ctypes.c_uint32(0)
+    rc = lib().r3_writeset_regions(bm.ctypes.data if bm.size else None, nbytes, page_bytes,
+                                   int(bool(want_dirty)), None, 0, ctypes.byref(n))
+    if rc not in (OK, ENOSPC):
+        raise R3Error(rc, "r3_writeset_regions")
+    out = np.zeros(n.value, dtype=REGION_DTYPE)
+    if n.value:
+        rc = lib().r3_writeset_regions(bm.ctypes.data, nbytes, page_bytes, int(bool(want_dirty)),
+                                       out.ctypes.data, n.value, ctypes.byref(n))
+        if rc != OK:
+            raise R3Error(rc, "r3_writeset_regions")
+    return out
+
+
+def r3_eval_candidate_guarded(ctx, restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, launch, user,
+                              warmup, reps, policy, d_regions, guard_tbl, d_expected, d_scratch,
+                              every=0, heal_tbl=None, stream=None):
+    """Returns (status, EvalResult, GuardResult)."""
+    _need(d_prologue, restore_tbl.arena_bytes, "prologue")
+    _need(d_epilogue, check_tbl.arena_bytes, "epilogue")
+    _need(d_live, max(restore_tbl.arena_bytes, check_tbl.arena_bytes, guard_tbl.arena_bytes), "live arena")
+    _need(d_regions, 40 * check_tbl.n, "region results")
+    _need(d_expected, 8 * guard_tbl.n, "guard checksums")
+    _need(d_scratch, 8 * guard_tbl.n, "guard scratch")
+    fn, usr, keep = _launch_args(launch, user)
+    g = Guard(guard_tbl.handle.value, _ptr(d_expected), _ptr(d_scratch),
+              heal_tbl.handle.value if heal_tbl is not None else None, every, 0)
+    out, gout = EvalResult(), GuardResult()
+    rc = lib().r3_eval_candidate_guarded(ctx.handle, restore_tbl.handle, _ptr(d_prologue),
+                                         check_tbl.handle, _ptr(d_epilogue), _ptr(d_live), fn, _ptr(usr),
+                                         warmup, reps, policy, _ptr(d_regions), ctypes.byref(out),
+                                         ctypes.byref(g), ctypes.byref(gout), _stream(stream))
+    del keep
+    if rc != ECANDIDATE:
+        ctx.check(rc, "r3_eval_candidate_guarded")
+    return rc, out, gout
 
 
 # ---- small conveniences for tests and the benchmark (no arithmetic of the method) --------

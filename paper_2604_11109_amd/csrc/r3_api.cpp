@@ -81,7 +81,12 @@ int r3_ctx_create(r3_ctx** out, int device) {
     delete ctx;
     return R3_EHIP;
   }
-  if (hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->pinned_dev), ctx->pinned, 0) != hipSuccess) {
+  if (hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->pinned_dev), ctx->pinned, 0) != hipSuccess ||
+      hipHostMalloc(reinterpret_cast<void**>(&ctx->guard_pinned), R3_MAX_REPLAYS * sizeof(r3::GuardSlot),
+                    hipHostMallocMapped) != hipSuccess ||
+      hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->guard_pinned_dev), ctx->guard_pinned, 0) !=
+          hipSuccess) {
+    if (ctx->guard_pinned) (void)hipHostFree(ctx->guard_pinned);
     (void)hipHostFree(ctx->pinned);
     delete ctx;
     return R3_EHIP;
@@ -95,6 +100,7 @@ int r3_ctx_destroy(r3_ctx* ctx) {
   DeviceGuard guard(ctx->device);
   for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
   if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+  if (ctx->guard_pinned) (void)hipHostFree(ctx->guard_pinned);
   delete ctx;
   return R3_OK;
 }
@@ -138,7 +144,9 @@ int r3_table_create(r3_ctx* ctx, const r3_region* host_tbl, uint32_t n, uint64_t
   if (reinterpret_cast<uintptr_t>(d_ws) & 255u) return fail(ctx, R3_EALIGN, "workspace not 256-byte aligned");
   r3::TablePlan plan;
   r3::plan_table(host_tbl, n, &plan);
-  if (plan.max_region_tiles > 0xFFFFFFu) return fail(ctx, R3_EINVAL, "region too large");
+  if (plan.max_region_tiles > 0xFFFFFFu || plan.max_shift - plan.min_shift >= r3::kMaxCopyClasses ||
+      plan.tiles.size() > 0xFFFFFFFFull)
+    return fail(ctx, R3_EINVAL, "region too large");
   const r3::WorkspaceLayout lay = r3::workspace_layout(n, plan.tiles.size());
   if (ws_bytes < lay.total) return fail(ctx, R3_ENOSPC, "workspace smaller than the table needs");
 
@@ -152,6 +160,9 @@ int r3_table_create(r3_ctx* ctx, const r3_region* host_tbl, uint32_t n, uint64_t
   if (e == hipSuccess && !plan.tiles.empty())
     e = hipMemcpy(ws + lay.tiles, plan.tiles.data(), plan.tiles.size() * sizeof(r3::Tile),
                   hipMemcpyHostToDevice);
+  if (e == hipSuccess && !plan.copy_tiles.empty())
+    e = hipMemcpy(ws + lay.copy_tiles, plan.copy_tiles.data(), plan.copy_tiles.size() * sizeof(r3::CopyTile),
+                  hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) return fail_hip(ctx, e, "table upload");
 
@@ -164,6 +175,8 @@ int r3_table_create(r3_ctx* ctx, const r3_region* host_tbl, uint32_t n, uint64_t
   tbl->dev.tile_begin = reinterpret_cast<const uint64_t*>(ws + lay.tile_begin);
   tbl->dev.tiles = reinterpret_cast<const r3::Tile*>(ws + lay.tiles);
   tbl->dev.partials = reinterpret_cast<r3::Partial*>(ws + lay.partials);
+  tbl->dev.copy_tiles = reinterpret_cast<const r3::CopyTile*>(ws + lay.copy_tiles);
+  std::memcpy(tbl->class_count, plan.class_count, sizeof(tbl->class_count));
   tbl->dev.n_regions = n;
   tbl->dev.min_shift = plan.min_shift;
   tbl->dev.cap_log2 = plan.cap_log2;
@@ -201,7 +214,7 @@ int r3_restore(r3_ctx* ctx, const r3_table* tbl, const void* d_snapshot, void* d
   if (s < l + tbl->arena_bytes && l < s + tbl->arena_bytes && tbl->arena_bytes)
     return fail(ctx, R3_EINVAL, "snapshot and live arenas overlap");
   DeviceGuard guard(ctx->device);
-  hipError_t e = r3::launch_restore(tbl->dev, d_snapshot, d_live, as_stream(stream));
+  hipError_t e = r3::launch_restore(tbl->dev, tbl->class_count, d_snapshot, d_live, as_stream(stream));
   return e == hipSuccess ? R3_OK : fail_hip(ctx, e, "restore launch");
 }
 
@@ -279,14 +292,25 @@ int r3_record(r3_ctx* ctx, const r3_table* tbl, void* d_live, r3_launch_fn launc
   return e == hipSuccess ? R3_OK : fail_hip(ctx, e, "record wait");
 }
 
-int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
-                      const r3_table* check_tbl, const void* d_epilogue, void* d_live,
-                      r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
-                      uint32_t compare_policy, r3_region_result* d_regions,
-                      r3_eval_result* host_out, void* stream) {
+static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
+                     const r3_table* check_tbl, const void* d_epilogue, void* d_live,
+                     r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
+                     uint32_t compare_policy, r3_region_result* d_regions, r3_eval_result* host_out,
+                     const r3_guard* guard, r3_guard_result* host_guard_out, void* stream) {
   int rc = check_common(ctx, restore_tbl);
   if (rc == R3_OK) rc = check_common(ctx, check_tbl);
   if (rc != R3_OK) return rc;
+  if (guard) {
+    rc = check_common(ctx, guard->guard_tbl);
+    if (rc == R3_OK && guard->heal_tbl) rc = check_common(ctx, guard->heal_tbl);
+    if (rc != R3_OK) return rc;
+    if (guard->d_expected == nullptr || guard->d_scratch == nullptr)
+      return fail(ctx, R3_EINVAL, "guard pointer is NULL");
+  }
+  if (host_guard_out) {
+    std::memset(host_guard_out, 0, sizeof(*host_guard_out));
+    host_guard_out->first_region = R3_NO_REGION;
+  }
   if (d_prologue == nullptr || d_epilogue == nullptr || d_live == nullptr || d_regions == nullptr ||
       host_out == nullptr)
     return fail(ctx, R3_EINVAL, "pointer is NULL");
@@ -297,7 +321,7 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
   if (reps == 0) return fail(ctx, R3_EINVAL, "reps must be at least 1");
   if (total > R3_MAX_REPLAYS) return fail(ctx, R3_ENOSPC, "warmup + reps exceeds R3_MAX_REPLAYS");
 
-  DeviceGuard guard(ctx->device);
+  DeviceGuard device_guard(ctx->device);
   hipStream_t s = as_stream(stream);
   // Events of replay r: [4r] before the restore and [4r+3] after the validation (only when
   // profiling), [4r+1] / [4r+2] around the candidate.
@@ -318,14 +342,17 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
   hipError_t e = hipSuccess;
   uint32_t done = 0;
   std::vector<uint8_t> validated(total, 0);
-  bool last_is_validation = false;  // the last work enqueued is a finalize pass that posts a seq
+  // The sequence number that the last work enqueued will post in pinned memory, if it does.
+  const uint64_t* last_flag = nullptr;
+  uint64_t last_want = 0;
+  std::vector<uint8_t> guarded(total, 0);
   for (uint32_t rep = 0; rep < total; ++rep) {
-    last_is_validation = false;
+    last_flag = nullptr;
     if (prof) {
       e = hipEventRecord(ctx->events[4 * rep], s);
       if (e != hipSuccess) break;
     }
-    e = r3::launch_restore(restore_tbl->dev, d_prologue, d_live, s);
+    e = r3::launch_restore(restore_tbl->dev, restore_tbl->class_count, d_prologue, d_live, s);
     if (e != hipSuccess) break;
     if (launch || prof) {
       e = hipEventRecord(ctx->events[4 * rep + 1], s);
@@ -347,7 +374,8 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
     if (validate) {
       e = r3::launch_compare(check_tbl->dev, d_live, d_epilogue, d_regions, nullptr,
                              &ctx->pinned_dev[n_validated], ++ctx->seq, s);
-      last_is_validation = true;
+      last_flag = &ctx->pinned[n_validated].seq;
+      last_want = ctx->seq;
       if (e != hipSuccess) break;
       ++n_validated;
       validated[rep] = 1;
@@ -356,6 +384,16 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
         if (e != hipSuccess) break;
       }
     }
+    if (guard && ((guard->every != 0 && (rep + 1) % guard->every == 0) || rep == total - 1)) {
+      e = r3::launch_checksum(guard->guard_tbl->dev, d_live, guard->d_scratch, s);
+      if (e == hipSuccess)
+        e = r3::launch_guard_compare(guard->d_scratch, guard->d_expected, guard->guard_tbl->dev.n_regions,
+                                     &ctx->guard_pinned_dev[rep], ++ctx->seq, s);
+      if (e != hipSuccess) break;
+      guarded[rep] = 1;
+      last_flag = &ctx->guard_pinned[rep].seq;
+      last_want = ctx->seq;
+    }
     ++done;
   }
   // Wait for the verdict.  When the last thing enqueued is a validation, its sequence number
@@ -363,12 +401,11 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
   // for it (bounded) avoids the wake-up latency of a stream wait.  Anything else, and any
   // doubt, takes the stream wait.
   bool arrived = false;
-  if (e == hipSuccess && cand == 0 && last_is_validation && n_validated) {
-    const volatile uint64_t* flag = &ctx->pinned[n_validated - 1].seq;
-    const uint64_t want = ctx->seq;
+  if (e == hipSuccess && cand == 0 && last_flag != nullptr) {
     for (uint32_t spin = 0; spin < (1u << 22) && !arrived; ++spin)
-      arrived = __atomic_load_n(const_cast<const uint64_t*>(flag), __ATOMIC_ACQUIRE) == want;
-    if (arrived && prof) arrived = hipEventSynchronize(ctx->events[4 * (total - 1) + 3]) == hipSuccess;
+      arrived = __atomic_load_n(last_flag, __ATOMIC_ACQUIRE) == last_want;
+    if (arrived && prof && validated[total - 1])
+      arrived = hipEventSynchronize(ctx->events[4 * (total - 1) + 3]) == hipSuccess;
   }
   if (!arrived) {
     hipError_t we = hipStreamSynchronize(s);
@@ -387,6 +424,30 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
     host_out->max_rel_err = last.max_rel_err;
   }
   host_out->pass = (cand == 0 && host_out->total_mismatch == 0) ? 1u : 0u;
+  if (guard) {
+    r3_guard_result g{};
+    g.first_region = R3_NO_REGION;
+    for (uint32_t rep = 0; rep < done; ++rep) {
+      if (!guarded[rep]) continue;
+      const r3::GuardSlot& gs = ctx->guard_pinned[rep];
+      ++g.checks;
+      if (gs.changed) {
+        if (g.failed_checks == 0) g.first_region = (uint32_t)gs.first_region;
+        ++g.failed_checks;
+        g.changed_regions = std::max(g.changed_regions, (uint32_t)gs.changed);
+      }
+    }
+    if (g.failed_checks) {
+      host_out->pass = 0;
+      if (guard->heal_tbl) {
+        hipError_t he = r3::launch_restore(guard->heal_tbl->dev, guard->heal_tbl->class_count, d_prologue, d_live, s);
+        if (he == hipSuccess) he = hipStreamSynchronize(s);
+        if (he != hipSuccess) return fail_hip(ctx, he, "heal restore");
+        g.healed = 1;
+      }
+    }
+    if (host_guard_out) *host_guard_out = g;
+  }
 
   // Candidate times of the replays after the warm-up that ran to the end.
   if (launch) {
@@ -425,6 +486,25 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
   }
   if (cand != 0) return fail(ctx, R3_ECANDIDATE, "the candidate failed to launch");
   return R3_OK;
+}
+
+int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
+                      const r3_table* check_tbl, const void* d_epilogue, void* d_live,
+                      r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
+                      uint32_t compare_policy, r3_region_result* d_regions,
+                      r3_eval_result* host_out, void* stream) {
+  return eval_impl(ctx, restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, launch, user, warmup,
+                   reps, compare_policy, d_regions, host_out, nullptr, nullptr, stream);
+}
+
+int r3_eval_candidate_guarded(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
+                              const r3_table* check_tbl, const void* d_epilogue, void* d_live,
+                              r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
+                              uint32_t compare_policy, r3_region_result* d_regions,
+                              r3_eval_result* host_out, const r3_guard* guard,
+                              r3_guard_result* host_guard_out, void* stream) {
+  return eval_impl(ctx, restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, launch, user, warmup,
+                   reps, compare_policy, d_regions, host_out, guard, host_guard_out, stream);
 }
 
 }  // extern "C"

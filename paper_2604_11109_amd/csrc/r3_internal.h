@@ -48,12 +48,31 @@ static_assert(sizeof(Partial) == 40, "partial layout");
 static_assert(sizeof(r3_region) == 40 && sizeof(r3_region_result) == 40, "ABI layout");
 static_assert(sizeof(r3_summary) == 40 && sizeof(r3_eval_result) == 56, "ABI layout");
 
+// Tiles grouped by size class (class c holds the tiles of 2^(min_shift + c) bytes) so that
+// the copy kernels can give every tile exactly as many 1 KiB wavefront slots as it has
+// bytes for, whatever mix of region sizes a table holds.
+constexpr uint32_t kMaxCopyClasses = 32;
+struct CopyClasses {
+  uint32_t n;                           // classes in use (max_shift - min_shift + 1)
+  uint32_t sub_log2[kMaxCopyClasses];   // log2 of the slots per tile of the class
+  uint32_t first[kMaxCopyClasses];      // first position of the class in copy_order
+  uint64_t slot_base[kMaxCopyClasses + 1];  // first slot of the class; [n] = all slots
+};
+
+// What a copy wavefront needs to know about its tile, in one 16-byte load.
+struct CopyTile {
+  uint64_t at;    // arena offset of the tile's first byte
+  uint32_t len;   // bytes in the tile
+  uint32_t es;    // element size of the region (unit of unaligned heads and tails)
+};
+
 // Device-side view of a table's workspace.
 struct TableDev {
   const r3_region* regions;   // n
   const uint64_t* tile_begin; // n + 1, prefix sum of tiles per region
   const Tile* tiles;          // n_tiles
   Partial* partials;          // n_tiles (checksum-only calls use the first 8 bytes * n_tiles)
+  const CopyTile* copy_tiles; // n_tiles: the tiles again, sorted by size class
   uint32_t n_regions;
   uint32_t min_shift;         // log2 of the smallest tile
   uint32_t cap_log2;          // log2 of the most tiles a region may have
@@ -72,16 +91,27 @@ struct HostSlot {
 };
 static_assert(sizeof(HostSlot) == 64, "host slot layout");
 
+// Pinned host slot of one guard check: how many regions changed, the first of them, and
+// the sequence number posted after both.
+struct GuardSlot {
+  uint64_t changed;
+  uint64_t first_region;
+  uint64_t seq;
+  uint64_t pad;
+};
+
 // Host-side plan of a table: how the regions split into tiles.
 struct TablePlan {
   uint32_t min_shift = 0, cap_log2 = 0, max_region_tiles = 0, max_shift = 0;
   uint64_t total_bytes = 0;
   std::vector<uint64_t> tile_begin;  // n + 1
   std::vector<Tile> tiles;
+  std::vector<CopyTile> copy_tiles;          // by size class, address order inside a class
+  uint32_t class_count[kMaxCopyClasses] = {};  // tiles per class
 };
 
 struct WorkspaceLayout {
-  size_t regions, tile_begin, tiles, partials, total;
+  size_t regions, tile_begin, tiles, partials, copy_tiles, total;
 };
 
 struct Tuning {
@@ -99,12 +129,15 @@ void plan_table(const r3_region* t, uint32_t n, TablePlan* plan);
 
 // Kernel launchers (r3_kernels.hip).  All enqueue on `s` and return the launch status.
 void set_copy_shape(uint32_t shift, uint32_t block);
-hipError_t launch_restore(const TableDev& t, const void* src, void* dst, hipStream_t s);
+hipError_t launch_restore(const TableDev& t, const uint32_t* class_count, const void* src, void* dst,
+                          hipStream_t s);
 hipError_t launch_copy_flat(const void* src, void* dst, uint64_t bytes, hipStream_t s);
 hipError_t launch_checksum(const TableDev& t, const void* arena, uint64_t* out, hipStream_t s);
 hipError_t launch_compare(const TableDev& t, const void* live, const void* golden,
                           r3_region_result* out, r3_summary* summary, HostSlot* host_slot,
                           uint64_t host_seq, hipStream_t s);
+hipError_t launch_guard_compare(const uint64_t* got, const uint64_t* expected, uint32_t n,
+                                GuardSlot* host_slot, uint64_t host_seq, hipStream_t s);
 hipError_t launch_dirty_diff(const void* pre, const void* post, uint64_t bytes, uint32_t page_bytes,
                              uint64_t* bitmap, uint64_t* dirty_count, hipStream_t s);
 
@@ -115,6 +148,8 @@ struct r3_ctx {
   std::string err;
   r3::HostSlot* pinned = nullptr;      // R3_MAX_REPLAYS slots, pinned host memory
   r3::HostSlot* pinned_dev = nullptr;  // the same memory as the device addresses it
+  r3::GuardSlot* guard_pinned = nullptr;      // R3_MAX_REPLAYS slots, pinned host memory
+  r3::GuardSlot* guard_pinned_dev = nullptr;
   uint64_t seq = 0;                    // sequence number of the last validation enqueued
   uint32_t profile_period = 0;         // 0 = off, n = stage events on every n-th evaluation
   uint64_t evals = 0;
@@ -127,4 +162,5 @@ struct r3_table {
   r3::TableDev dev{};
   uint64_t arena_bytes = 0;
   uint64_t total_bytes = 0;
+  uint32_t class_count[r3::kMaxCopyClasses] = {};
 };

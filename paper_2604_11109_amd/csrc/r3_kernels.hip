@@ -231,19 +231,26 @@ __device__ __forceinline__ uint32_t elem_size_dev(uint32_t dtype) {
 // 5.1-5.4 TB/s for wavefronts that walk 64 KiB or more.  A table tile is therefore spread
 // over 2^sub_log2 consecutive wavefront slots; slots past the end of a tile exit at once.
 template <int BLOCK>
-__global__ __launch_bounds__(BLOCK) void restore_kernel(TableDev t, const uint8_t* src, uint8_t* dst,
-                                                        uint32_t sub_log2, uint32_t copy_shift) {
+__global__ __launch_bounds__(BLOCK) void restore_kernel(TableDev t, CopyClasses cls, const uint8_t* src,
+                                                        uint8_t* dst, uint32_t copy_shift) {
   const uint64_t slot = (uint64_t)blockIdx.x * (BLOCK / 64) + wave_in_block();
-  const uint64_t tile_id = slot >> sub_log2;
-  if (tile_id >= t.n_tiles) return;
-  const uint32_t sub = (uint32_t)(slot & ((1ull << sub_log2) - 1));
-  const TileView tv = resolve_tile(t, tile_id);
+  if (slot >= cls.slot_base[cls.n]) return;
+  uint32_t c = 0;  // size class of this slot: a short scalar scan of the launch arguments
+  while (c + 1 < cls.n && slot >= cls.slot_base[c + 1]) ++c;
+  const uint64_t rel = slot - cls.slot_base[c];
+  const uint32_t sub_log2 = cls.sub_log2[c];
+  const CopyTile* ct = &t.copy_tiles[cls.first[c] + (rel >> sub_log2)];
+  const uint64_t tile_at = sgpr(ct->at);
+  const uint32_t tile_len = sgpr(ct->len), es = sgpr(ct->es);
+  const uint32_t sub = (uint32_t)(rel & ((1ull << sub_log2) - 1));
   const uint64_t begin = (uint64_t)sub << copy_shift;
-  if (begin >= tv.len) return;
-  const uint32_t left = tv.len - (uint32_t)begin;
-  const uint32_t len = left < (1u << copy_shift) ? left : (1u << copy_shift);
-  const uint64_t at = tv.offset + tv.rel_start + begin;
-  copy_span(src + at, dst + at, len, elem_size_dev(tv.dtype), lane_id());
+  if (begin >= tile_len) return;
+  const uint32_t left = tile_len - (uint32_t)begin;
+  // a class whose tiles are smaller than the copy unit has one slot per tile
+  const uint32_t unit = sub_log2 ? (1u << copy_shift) : 0xFFFFFFFFu;
+  const uint32_t len = left < unit ? left : unit;
+  const uint64_t at = tile_at + begin;
+  copy_span(src + at, dst + at, len, es, lane_id());
 }
 
 // Whole-range copy for r3_record: wavefront k moves bytes [k << copy_shift, (k+1) << copy_shift).
@@ -944,6 +951,40 @@ __global__ __launch_bounds__(kBlock) void popcount_kernel(const uint64_t* bitmap
   }
 }
 
+// Guard check: how many of n checksums differ from the recorded ones, and the first such
+// region; one block, result straight into pinned host memory.
+__global__ __launch_bounds__(kBlock) void guard_compare_kernel(const uint64_t* got,
+                                                               const uint64_t* expected, uint32_t n,
+                                                               GuardSlot* host_slot, uint64_t host_seq) {
+  __shared__ uint32_t sh_count[kWavesPerBlock], sh_first[kWavesPerBlock];
+  uint32_t count = 0, first = R3_NO_REGION;
+  for (uint32_t i = threadIdx.x; i < n; i += kBlock) {
+    if (got[i] != expected[i]) {
+      ++count;
+      first = i < first ? i : first;
+    }
+  }
+  count = wave_sum(count);
+  first = wave_min(first);
+  if ((threadIdx.x & 63) == 0) {
+    sh_count[threadIdx.x >> 6] = count;
+    sh_first[threadIdx.x >> 6] = first;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    count = 0;
+    first = R3_NO_REGION;
+    for (int w = 0; w < kWavesPerBlock; ++w) {
+      count += sh_count[w];
+      first = sh_first[w] < first ? sh_first[w] : first;
+    }
+    host_slot->changed = count;
+    host_slot->first_region = first;
+    __threadfence_system();
+    __hip_atomic_store(&host_slot->seq, host_seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+  }
+}
+
 uint32_t grid_for(uint64_t tiles) { return (uint32_t)((tiles + kWavesPerBlock - 1) / kWavesPerBlock); }
 
 }  // namespace
@@ -959,19 +1000,31 @@ void set_copy_shape(uint32_t shift, uint32_t block) {
   g_copy_block = block;
 }
 
-hipError_t launch_restore(const TableDev& t, const void* src, void* dst, hipStream_t s) {
+hipError_t launch_restore(const TableDev& t, const uint32_t* class_count, const void* src, void* dst,
+                          hipStream_t s) {
   if (t.n_tiles == 0) return hipSuccess;
   const uint32_t cs = g_copy_shift, wpb = g_copy_block / 64;
-  const uint32_t sub_log2 = t.max_shift > cs ? t.max_shift - cs : 0;
-  const uint64_t slots = t.n_tiles << sub_log2;
+  CopyClasses cls{};
+  cls.n = t.max_shift - t.min_shift + 1;
+  uint64_t slots = 0;
+  uint32_t first = 0;
+  for (uint32_t c = 0; c < cls.n; ++c) {
+    const uint32_t shift = t.min_shift + c;
+    cls.sub_log2[c] = shift > cs ? shift - cs : 0;
+    cls.first[c] = first;
+    cls.slot_base[c] = slots;
+    slots += (uint64_t)class_count[c] << cls.sub_log2[c];
+    first += class_count[c];
+  }
+  cls.slot_base[cls.n] = slots;
   const uint64_t blocks = (slots + wpb - 1) / wpb;
   if (blocks > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
   const uint8_t* a = (const uint8_t*)src;
   uint8_t* b = (uint8_t*)dst;
   switch (g_copy_block) {
-    case 64: restore_kernel<64><<<(uint32_t)blocks, 64, 0, s>>>(t, a, b, sub_log2, cs); break;
-    case 128: restore_kernel<128><<<(uint32_t)blocks, 128, 0, s>>>(t, a, b, sub_log2, cs); break;
-    default: restore_kernel<256><<<(uint32_t)blocks, 256, 0, s>>>(t, a, b, sub_log2, cs); break;
+    case 64: restore_kernel<64><<<(uint32_t)blocks, 64, 0, s>>>(t, cls, a, b, cs); break;
+    case 128: restore_kernel<128><<<(uint32_t)blocks, 128, 0, s>>>(t, cls, a, b, cs); break;
+    default: restore_kernel<256><<<(uint32_t)blocks, 256, 0, s>>>(t, cls, a, b, cs); break;
   }
   return hipGetLastError();
 }
@@ -1036,6 +1089,12 @@ hipError_t launch_compare(const TableDev& t, const void* live, const void* golde
     e = hipGetLastError();
   }
   return e;
+}
+
+hipError_t launch_guard_compare(const uint64_t* got, const uint64_t* expected, uint32_t n,
+                                GuardSlot* host_slot, uint64_t host_seq, hipStream_t s) {
+  guard_compare_kernel<<<1, kBlock, 0, s>>>(got, expected, n, host_slot, host_seq);
+  return hipGetLastError();
 }
 
 hipError_t launch_dirty_diff(const void* pre, const void* post, uint64_t bytes, uint32_t page_bytes,

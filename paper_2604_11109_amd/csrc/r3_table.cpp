@@ -53,6 +53,7 @@ WorkspaceLayout workspace_layout(uint32_t n, uint64_t tiles) {
   w.tile_begin = at;  at += up256(((size_t)n + 1) * sizeof(uint64_t));
   w.tiles = at;       at += up256((size_t)tiles * sizeof(Tile));
   w.partials = at;    at += up256((size_t)tiles * sizeof(Partial));
+  w.copy_tiles = at;  at += up256((size_t)tiles * sizeof(CopyTile));
   w.total = at;
   return w;
 }
@@ -104,10 +105,33 @@ void plan_table(const r3_region* t, uint32_t n, TablePlan* plan) {
   }
   plan->tile_begin[n] = count;
   plan->tiles.resize(count);
+  for (uint32_t c = 0; c < kMaxCopyClasses; ++c) plan->class_count[c] = 0;
   for (uint32_t i = 0; i < n; ++i) {
     uint32_t s = tile_shift(t[i].bytes, tu.min_shift, tu.cap_log2);
     uint64_t k = plan->tile_begin[i], e = plan->tile_begin[i + 1];
     for (uint32_t j = 0; k < e; ++k, ++j) plan->tiles[k] = Tile{i, j | (s << 24)};
+    const uint32_t c = s - tu.min_shift;
+    if (c < kMaxCopyClasses) plan->class_count[c] += (uint32_t)(e - plan->tile_begin[i]);
+  }
+  // Counting sort of the tile ids by class, address order kept inside a class.
+  uint64_t at[kMaxCopyClasses];
+  uint64_t run = 0;
+  for (uint32_t c = 0; c < kMaxCopyClasses; ++c) {
+    at[c] = run;
+    run += plan->class_count[c];
+  }
+  plan->copy_tiles.assign(count, CopyTile{0, 0, 0});
+  for (uint64_t k = 0; k < count; ++k) {
+    const Tile& tl = plan->tiles[k];
+    const uint32_t shift = tl.packed >> 24, index = tl.packed & 0xFFFFFFu;
+    const uint32_t c = shift - tu.min_shift;
+    if (c >= kMaxCopyClasses) continue;
+    const r3_region& rg = t[tl.region];
+    const uint64_t rel = (uint64_t)index << shift;
+    const uint64_t left = rg.bytes - rel;
+    const uint64_t full = 1ull << shift;
+    plan->copy_tiles[at[c]++] = CopyTile{rg.offset + rel, (uint32_t)(left < full ? left : full),
+                                          elem_size(rg.dtype)};
   }
 }
 
@@ -127,6 +151,42 @@ size_t r3_table_workspace_bytes_exact(const r3_region* host_tbl, uint32_t n,
                                       uint64_t arena_bytes) {
   if (r3::validate_table(host_tbl, n, arena_bytes) != R3_OK) return 0;
   return r3::workspace_layout(n, r3::count_tiles(host_tbl, n)).total;
+}
+
+int r3_writeset_regions(const uint64_t* host_bitmap, uint64_t bytes, uint32_t page_bytes,
+                        int want_dirty, r3_region* out, uint32_t cap, uint32_t* n_out) {
+  if (n_out == nullptr || page_bytes == 0 || (bytes && host_bitmap == nullptr) || (cap && out == nullptr))
+    return R3_EINVAL;
+  const uint64_t n_pages = (bytes + page_bytes - 1) / page_bytes;
+  uint64_t runs = 0, start = 0;
+  bool in_run = false;
+  auto close_run = [&](uint64_t end_page) {
+    if (runs < cap) {
+      r3_region r{};
+      r.offset = start * page_bytes;
+      const uint64_t end = end_page * page_bytes;
+      r.bytes = (end < bytes ? end : bytes) - r.offset;
+      r.dtype = R3_U8;
+      r.mode = R3_CMP_BITWISE;
+      out[runs] = r;
+    }
+    ++runs;
+  };
+  for (uint64_t p = 0; p < n_pages; ++p) {
+    const bool dirty = (host_bitmap[p >> 6] >> (p & 63)) & 1u;
+    const bool want = dirty == (want_dirty != 0);
+    if (want && !in_run) {
+      in_run = true;
+      start = p;
+    } else if (!want && in_run) {
+      in_run = false;
+      close_run(p);
+    }
+  }
+  if (in_run) close_run(n_pages);
+  if (runs > 0xFFFFFFFFull) return R3_ERANGE;
+  *n_out = (uint32_t)runs;
+  return runs > cap ? R3_ENOSPC : R3_OK;
 }
 
 int r3_tune_tiles(uint32_t min_tile_bytes, uint32_t max_tiles_per_region) {

@@ -595,10 +595,81 @@ def check_record(api, seed=18):
     assert int(rec["epi_cs"][1]) == brute_checksum(live[4096:].tobytes())
 
 
+def check_writeset_regions(api, seed=19):
+    rng = np.random.default_rng(seed)
+    for nbytes, page in [(70 * 4096 + 123, 4096), (4096, 4096), (1, 4096), (64 * 256, 256), (129 * 512 + 511, 512)]:
+        npages = -(-nbytes // page)
+        for density in (0.0, 0.05, 0.5, 1.0):
+            bits = rng.random(npages) < density
+            bm = np.zeros(-(-npages // 64), dtype=np.uint64)
+            for p in np.flatnonzero(bits):
+                bm[p // 64] |= np.uint64(1) << np.uint64(p % 64)
+            for want in (1, 0):
+                t = api.writeset_regions(bm, nbytes, page, want)
+                # brute force: a byte is covered iff its page has the wanted state
+                covered = np.zeros(nbytes, dtype=np.int32)
+                for r in t:
+                    assert int(r["bytes"]) > 0 and int(r["dtype"]) == api.U8 and int(r["mode"]) == api.BITWISE
+                    covered[int(r["offset"]):int(r["offset"]) + int(r["bytes"])] += 1
+                wanted = np.repeat(bits == bool(want), page)[:nbytes]
+                assert (covered == wanted.astype(np.int32)).all()
+                # maximal runs in address order: consecutive regions never touch
+                ends = t["offset"] + t["bytes"]
+                assert (t["offset"][1:] > ends[:-1]).all() if len(t) > 1 else True
+                assert api.validate_table(t, nbytes) == (api.OK if len(t) else api.EINVAL)
+    assert len(api.writeset_regions(np.zeros(0, np.uint64), 0, 4096, 1)) == 0
+
+
+def check_eval_guard(api, seed=20):
+    rng = np.random.default_rng(seed)
+    P = 256
+    n = 16 * P
+    pro = rng.integers(0, 256, size=n, dtype=np.uint8)
+    def kernel(live):                      # writes pages 3 and 9..10 only
+        live[3 * P + 7] ^= 0x11
+        live[9 * P:11 * P] = live[0:2 * P] + 1
+    rec_live = pro.copy()
+    full = api.make_table([(0, n, api.U8, api.BITWISE, 0, 0)])
+    rec = api.record(full, rec_live, kernel, page_bytes=P)
+    assert [int(x) for x in rec["bitmap"]] == [(1 << 3) | (1 << 9) | (1 << 10)] and rec["dirty_count"] == 3
+    dirty = api.writeset_regions(rec["bitmap"], n, P, 1)
+    clean = api.writeset_regions(rec["bitmap"], n, P, 0)
+    assert [(int(r["offset"]), int(r["bytes"])) for r in dirty] == [(3 * P, P), (9 * P, 2 * P)]
+    assert [(int(r["offset"]), int(r["bytes"])) for r in clean] == [(0, 3 * P), (4 * P, 5 * P), (11 * P, 5 * P)]
+    expected = api.checksum(clean, rec["prologue"])
+    assert (expected == api.checksum(clean, rec["epilogue"])).all()
+    live = pro.copy()
+    # a well-behaved candidate: write-set restore is enough, guard stays quiet
+    out = api.eval_candidate(dirty, rec["prologue"], dirty, rec["epilogue"], live, kernel, 1, 3,
+                             guard_tbl=clean, guard_expected=expected, guard_every=2, heal_tbl=full)
+    assert out["pass"] == 1 and out["guard"] == {"checks": 2, "failed_checks": 0, "changed_regions": 0,
+                                                  "first_region": api.NO_REGION, "healed": 0}
+    # a candidate with a stray write outside the write-set on its second replay: the validated
+    # regions still match, only the guard can tell; healing puts the recorded state back
+    calls = {"k": 0}
+    def stray(live):
+        kernel(live)
+        if calls["k"] >= 1:
+            live[12 * P + 1] = (int(pro[12 * P + 1]) + 1) & 0xFF
+        calls["k"] += 1
+    out = api.eval_candidate(dirty, rec["prologue"], dirty, rec["epilogue"], live, stray, 0, 4,
+                             guard_tbl=clean, guard_expected=expected, guard_every=1, heal_tbl=full)
+    assert out["total_mismatch"] == 0 and out["pass"] == 0
+    assert out["guard"] == {"checks": 4, "failed_checks": 3, "changed_regions": 1, "first_region": 2, "healed": 1}
+    assert (live == rec["prologue"]).all()
+    # without healing the damage stays
+    calls["k"] = 0
+    live2 = pro.copy()
+    out = api.eval_candidate(dirty, rec["prologue"], dirty, rec["epilogue"], live2, stray, 0, 2,
+                             guard_tbl=clean, guard_expected=expected, guard_every=0)
+    assert out["guard"]["checks"] == 1 and out["guard"]["failed_checks"] == 1 and out["guard"]["healed"] == 0
+    assert live2[12 * P + 1] != pro[12 * P + 1]
+
+
 ALL_CHECKS = [
     check_checksum_constants, check_checksum_golden, check_checksum_bruteforce,
     check_checksum_properties, check_checksum_table, check_compare_bruteforce,
     check_compare_worked_example, check_compare_isclose, check_compare_closed_forms,
     check_compare_unfused, check_summary, check_restore, check_dirty_diff, check_table_rules,
-    check_eval_loop, check_record,
+    check_eval_loop, check_record, check_writeset_regions, check_eval_guard,
 ]

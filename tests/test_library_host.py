@@ -107,3 +107,19 @@ def test_no_gpu_calls_fail_cleanly(r3):
     with pytest.raises(r3.R3Error) as e:
         r3.Context(0)
     assert e.value.status == r3.EHIP
+
+
+def test_writeset_regions_agree_with_oracle(r3, oracle):
+    rng = np.random.default_rng(8)
+    for nbytes, page in [(70 * 4096 + 123, 4096), (4096, 4096), (1, 4096), (64 * 256, 256), (1000 * 512 + 5, 512)]:
+        npages = -(-nbytes // page)
+        for density in (0.0, 0.02, 0.3, 0.97, 1.0):
+            bits = rng.random(npages) < density
+            bm = np.zeros(-(-npages // 64), dtype=np.uint64)
+            for p in np.flatnonzero(bits):
+                bm[p // 64] |= np.uint64(1) << np.uint64(p % 64)
+            for want in (1, 0):
+                a = r3.r3_writeset_regions(bm, nbytes, page, want)
+                b = oracle.writeset_regions(bm, nbytes, page, want)
+                assert a.tobytes() == b.tobytes(), (nbytes, page, density, want)
+    assert len(r3.r3_writeset_regions(np.zeros(0, np.uint64), 0, 4096, 1)) == 0
