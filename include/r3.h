@@ -320,6 +320,51 @@ int r3_eval_candidate_guarded(r3_ctx* ctx, const r3_table* restore_tbl, const vo
                               r3_eval_result* host_out, const r3_guard* guard,
                               r3_guard_result* host_guard_out, void* stream);
 
+/* ---- several recorded instances of one kernel --------------------------- */
+
+/* Section V-C: promising candidates are validated against additional recorded instances of
+ * the same kernel.  Instances are laid out back to back in "super arenas": instance i of the
+ * prologue, epilogue and live state occupies [i*instance_stride, i*instance_stride + arena).
+ * r3_table_replicate writes `instances` copies of an n-region table, copy i shifted by
+ * i*instance_stride, to out (host, n*instances regions): tables created from it restore and
+ * validate all instances in one launch each. */
+int r3_table_replicate(const r3_region* host_tbl, uint32_t n, uint64_t instance_stride,
+                       uint32_t instances, r3_region* out);
+
+/* r3_eval_candidate over `instances` recorded instances: per replay one restore launch (all
+ * instances), `instances` calls of the launch callback (call i gets d_live + i*instance_stride;
+ * their total time is the replay's candidate time) and one validation launch (all instances).
+ * restore_tbl and check_tbl are tables over the super arena (see r3_table_replicate);
+ * check_tbl's region count must be a multiple of `instances`, copy i holding instance i's
+ * regions.  host_instance_pass (host, `instances` bytes, may be NULL): 1 where every region of
+ * that instance matched in the last validated replay.  Waits for the stream. */
+int r3_eval_candidate_instances(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologues,
+                                const r3_table* check_tbl, const void* d_epilogues, void* d_live,
+                                r3_launch_fn launch, void* user, uint32_t instances,
+                                uint64_t instance_stride, uint32_t warmup, uint32_t reps,
+                                uint32_t compare_policy, r3_region_result* d_regions,
+                                r3_eval_result* host_out, uint8_t* host_instance_pass, void* stream);
+
+/* ---- timing statistics -------------------------------------------------- */
+
+/* Candidate times (ms) of the timed replays of the last evaluation on ctx, in replay order:
+ * copies at most cap values to out (host) and the number available to *n_out. */
+int r3_ctx_last_times(const r3_ctx* ctx, float* out, uint32_t cap, uint32_t* n_out);
+
+/* What a driver needs to decide whether a runtime is trustworthy (Section IV: each
+ * experiment is replayed K times; Section VII-B: warm-up runs are discarded). */
+typedef struct {
+  uint32_t n;       /* samples used                                              */
+  uint32_t stable;  /* 1 if mad / median <= rel_noise                            */
+  float min, median, max, mean;
+  float mad;        /* median of |x - median|                                    */
+  float reserved;
+} r3_timing;
+
+/* Host only: statistics of n samples; rel_noise is the stability bound on mad/median.
+ * n == 0 gives zeros and stable = 0. */
+int r3_timing_stats(const float* ms, uint32_t n, float rel_noise, r3_timing* out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -187,6 +187,52 @@ def writeset_regions(bitmap, nbytes, page_bytes, want_dirty):
     return make_table(rows)
 
 
+def replicate_table(tbl, instance_stride, instances):
+    """`instances` copies of a table, copy i shifted by i*instance_stride (several recorded
+    instances of one kernel laid out back to back, Section V-C)."""
+    t = _tbl(tbl)
+    rows = []
+    for i in range(instances):
+        for r in t:
+            rows.append((int(r["offset"]) + i * instance_stride, int(r["bytes"]), int(r["dtype"]),
+                         int(r["mode"]), float(r["rtol"]), float(r["atol"])))
+    return make_table(rows)
+
+
+def eval_candidate_instances(restore_tbl, prologues, check_tbl, epilogues, live, launch, instances,
+                             instance_stride, warmup=0, reps=1, policy=EVERY):
+    """eval_candidate over several recorded instances: launch(view, i) runs the candidate on
+    instance i's part of the live super arena.  Adds instance_pass (last validated replay)."""
+    def all_instances(arena):
+        for i in range(instances):
+            rc = launch(arena[i * instance_stride:], i)
+            if rc:
+                return rc
+        return 0
+    out = eval_candidate(restore_tbl, prologues, check_tbl, epilogues, live, all_instances, warmup, reps, policy)
+    per = len(check_tbl) // instances
+    flags = np.zeros(instances, dtype=np.uint8)
+    if out["regions"] is not None:
+        for i in range(instances):
+            flags[i] = int(out["candidate_status"] == 0
+                           and (out["regions"]["mismatch_count"][i * per:(i + 1) * per] == 0).all())
+    out["instance_pass"] = flags
+    return out
+
+
+def timing_stats(ms, rel_noise):
+    """min, median, max, mean, median absolute deviation and the stability flag of a set of
+    replay times (plain definitions)."""
+    x = np.sort(np.asarray(ms, dtype=np.float32))
+    if x.size == 0:
+        return {"n": 0, "stable": 0, "min": 0.0, "median": 0.0, "max": 0.0, "mean": 0.0, "mad": 0.0}
+    med = np.float32(np.median(x))
+    mad = np.float32(np.median(np.abs(x - med)))
+    return {"n": int(x.size), "stable": int(med > 0 and mad <= np.float32(rel_noise) * med),
+            "min": float(x[0]), "median": float(med), "max": float(x[-1]),
+            "mean": float(np.float32(x.astype(np.float64).sum() / x.size)), "mad": float(mad)}
+
+
 def record(tbl, live, launch, page_bytes=4096):
     """Section V-A: keep the state before and after one run of the recorded kernel.
 

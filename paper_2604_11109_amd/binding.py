@@ -58,6 +58,12 @@ class GuardResult(ctypes.Structure):
                 ("healed", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
+class Timing(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_uint32), ("stable", ctypes.c_uint32), ("min", ctypes.c_float),
+                ("median", ctypes.c_float), ("max", ctypes.c_float), ("mean", ctypes.c_float),
+                ("mad", ctypes.c_float), ("reserved", ctypes.c_float)]
+
+
 LAUNCH_FN = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p)
 
 DECLARED = [
@@ -66,7 +72,8 @@ DECLARED = [
     "r3_table_validate", "r3_table_workspace_bytes", "r3_table_workspace_bytes_exact",
     "r3_tune_tiles", "r3_tune_copy", "r3_table_create", "r3_table_destroy", "r3_table_info", "r3_restore",
     "r3_checksum", "r3_compare", "r3_dirty_diff", "r3_record", "r3_eval_candidate",
-    "r3_writeset_regions", "r3_eval_candidate_guarded",
+    "r3_writeset_regions", "r3_eval_candidate_guarded", "r3_table_replicate",
+    "r3_eval_candidate_instances", "r3_ctx_last_times", "r3_timing_stats",
 ]
 
 _lib = None
@@ -119,6 +126,11 @@ def lib():
         L.r3_eval_candidate_guarded.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, u32, vp,
                                                 ctypes.POINTER(EvalResult), ctypes.POINTER(Guard),
                                                 ctypes.POINTER(GuardResult), vp]
+        L.r3_table_replicate.argtypes = [vp, u32, u64, u32, vp]
+        L.r3_eval_candidate_instances.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, u64, u32, u32, u32,
+                                                  vp, ctypes.POINTER(EvalResult), vp, vp]
+        L.r3_ctx_last_times.argtypes = [vp, vp, u32, ctypes.POINTER(u32)]
+        L.r3_timing_stats.argtypes = [vp, u32, ctypes.c_float, ctypes.POINTER(Timing)]
         for name in DECLARED:
             getattr(L, name)  # AttributeError if the library does not export it
         _lib = L
@@ -222,6 +234,14 @@ class Context:
         self.check(lib().r3_ctx_profile_read(self.handle, ctypes.byref(p), int(bool(reset))),
                    "r3_ctx_profile_read")
         return p
+
+    def last_times(self):
+        """Candidate times (ms) of the timed replays of the last evaluation."""
+        n = ctypes.c_uint32(0)
+        buf = np.zeros(MAX_REPLAYS, dtype=np.float32)
+        self.check(lib().r3_ctx_last_times(self.handle, buf.ctypes.data, buf.size, ctypes.byref(n)),
+                   "r3_ctx_last_times")
+        return buf[:n.value].copy()
 
     def close(self):
         if self.handle:
@@ -408,6 +428,45 @@ def r3_eval_candidate_guarded(ctx, restore_tbl, d_prologue, check_tbl, d_epilogu
     if rc != ECANDIDATE:
         ctx.check(rc, "r3_eval_candidate_guarded")
     return rc, out, gout
+
+
+def r3_table_replicate(tbl, instance_stride, instances):
+    t = _host_table(tbl)
+    out = np.zeros(len(t) * instances, dtype=REGION_DTYPE)
+    rc = lib().r3_table_replicate(t.ctypes.data if len(t) else None, len(t), instance_stride, instances,
+                                  out.ctypes.data if out.size else None)
+    if rc != OK:
+        raise R3Error(rc, "r3_table_replicate")
+    return out
+
+
+def r3_eval_candidate_instances(ctx, restore_tbl, d_prologues, check_tbl, d_epilogues, d_live, launch, user,
+                                instances, instance_stride, warmup, reps, policy, d_regions, stream=None):
+    """Returns (status, EvalResult, per-instance pass flags as a uint8 array)."""
+    _need(d_prologues, restore_tbl.arena_bytes, "prologues")
+    _need(d_epilogues, check_tbl.arena_bytes, "epilogues")
+    _need(d_live, max(restore_tbl.arena_bytes, check_tbl.arena_bytes), "live arena")
+    _need(d_regions, 40 * check_tbl.n, "region results")
+    fn, usr, keep = _launch_args(launch, user)
+    out = EvalResult()
+    flags = np.zeros(instances, dtype=np.uint8)
+    rc = lib().r3_eval_candidate_instances(ctx.handle, restore_tbl.handle, _ptr(d_prologues), check_tbl.handle,
+                                           _ptr(d_epilogues), _ptr(d_live), fn, _ptr(usr), instances,
+                                           instance_stride, warmup, reps, policy, _ptr(d_regions),
+                                           ctypes.byref(out), flags.ctypes.data, _stream(stream))
+    del keep
+    if rc != ECANDIDATE:
+        ctx.check(rc, "r3_eval_candidate_instances")
+    return rc, out, flags
+
+
+def r3_timing_stats(ms, rel_noise):
+    a = np.ascontiguousarray(ms, dtype=np.float32)
+    out = Timing()
+    rc = lib().r3_timing_stats(a.ctypes.data if a.size else None, a.size, rel_noise, ctypes.byref(out))
+    if rc != OK:
+        raise R3Error(rc, "r3_timing_stats")
+    return out
 
 
 # ---- small conveniences for tests and the benchmark (no arithmetic of the method) --------

@@ -296,7 +296,8 @@ static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pro
                      const r3_table* check_tbl, const void* d_epilogue, void* d_live,
                      r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
                      uint32_t compare_policy, r3_region_result* d_regions, r3_eval_result* host_out,
-                     const r3_guard* guard, r3_guard_result* host_guard_out, void* stream) {
+                     const r3_guard* guard, r3_guard_result* host_guard_out, uint32_t instances,
+                     uint64_t instance_stride, void* stream) {
   int rc = check_common(ctx, restore_tbl);
   if (rc == R3_OK) rc = check_common(ctx, check_tbl);
   if (rc != R3_OK) return rc;
@@ -359,9 +360,11 @@ static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pro
       if (e != hipSuccess) break;
     }
     if (launch) {
-      cand = launch(user, d_live, stream);
-      hipError_t le = hipGetLastError();
-      if (cand == 0 && le != hipSuccess) cand = -(int)le;
+      for (uint32_t inst = 0; inst < instances && cand == 0; ++inst) {
+        cand = launch(user, static_cast<uint8_t*>(d_live) + (uint64_t)inst * instance_stride, stream);
+        hipError_t le = hipGetLastError();
+        if (cand == 0 && le != hipSuccess) cand = -(int)le;
+      }
       if (cand != 0) break;
     }
     if (launch || prof) {
@@ -450,6 +453,7 @@ static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pro
   }
 
   // Candidate times of the replays after the warm-up that ran to the end.
+  ctx->last_times.clear();
   if (launch) {
     std::vector<float> ms;
     for (uint32_t rep = warmup; rep < done; ++rep) {
@@ -457,6 +461,7 @@ static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pro
       if (hipEventElapsedTime(&t, ctx->events[4 * rep + 1], ctx->events[4 * rep + 2]) == hipSuccess)
         ms.push_back(t);
     }
+    ctx->last_times = ms;
     if (!ms.empty()) {
       std::sort(ms.begin(), ms.end());
       host_out->ms_min = ms.front();
@@ -494,7 +499,7 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
                       uint32_t compare_policy, r3_region_result* d_regions,
                       r3_eval_result* host_out, void* stream) {
   return eval_impl(ctx, restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, launch, user, warmup,
-                   reps, compare_policy, d_regions, host_out, nullptr, nullptr, stream);
+                   reps, compare_policy, d_regions, host_out, nullptr, nullptr, 1, 0, stream);
 }
 
 int r3_eval_candidate_guarded(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
@@ -504,7 +509,48 @@ int r3_eval_candidate_guarded(r3_ctx* ctx, const r3_table* restore_tbl, const vo
                               r3_eval_result* host_out, const r3_guard* guard,
                               r3_guard_result* host_guard_out, void* stream) {
   return eval_impl(ctx, restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, launch, user, warmup,
-                   reps, compare_policy, d_regions, host_out, guard, host_guard_out, stream);
+                   reps, compare_policy, d_regions, host_out, guard, host_guard_out, 1, 0, stream);
+}
+
+int r3_eval_candidate_instances(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologues,
+                                const r3_table* check_tbl, const void* d_epilogues, void* d_live,
+                                r3_launch_fn launch, void* user, uint32_t instances,
+                                uint64_t instance_stride, uint32_t warmup, uint32_t reps,
+                                uint32_t compare_policy, r3_region_result* d_regions,
+                                r3_eval_result* host_out, uint8_t* host_instance_pass, void* stream) {
+  if (ctx == nullptr) return R3_EINVAL;
+  if (instances == 0 || check_tbl == nullptr || check_tbl->dev.n_regions % instances != 0)
+    return fail(ctx, R3_EINVAL, "check table is not a whole number of instances");
+  if (instance_stride & 15u) return fail(ctx, R3_EALIGN, "instance stride not a multiple of 16");
+  if (instances > 1 && (check_tbl->arena_bytes < (uint64_t)(instances - 1) * instance_stride ||
+                        (restore_tbl && restore_tbl->arena_bytes < (uint64_t)(instances - 1) * instance_stride)))
+    return fail(ctx, R3_ERANGE, "instances reach past the super arena");
+  int rc = eval_impl(ctx, restore_tbl, d_prologues, check_tbl, d_epilogues, d_live, launch, user, warmup,
+                     reps, compare_policy, d_regions, host_out, nullptr, nullptr, instances,
+                     instance_stride, stream);
+  if ((rc == R3_OK || rc == R3_ECANDIDATE) && host_instance_pass) {
+    const uint32_t n = check_tbl->dev.n_regions, per = n / instances;
+    std::vector<r3_region_result> res(n);
+    DeviceGuard device_guard(ctx->device);
+    hipError_t e = hipMemcpyAsync(res.data(), d_regions, (size_t)n * sizeof(r3_region_result),
+                                  hipMemcpyDeviceToHost, as_stream(stream));
+    if (e == hipSuccess) e = hipStreamSynchronize(as_stream(stream));
+    if (e != hipSuccess) return fail_hip(ctx, e, "instance verdicts");
+    for (uint32_t i = 0; i < instances; ++i) {
+      uint8_t ok = host_out->candidate_status == 0 ? 1 : 0;
+      for (uint32_t r = 0; r < per; ++r)
+        if (res[(size_t)i * per + r].mismatch_count != 0) ok = 0;
+      host_instance_pass[i] = ok;
+    }
+  }
+  return rc;
+}
+
+int r3_ctx_last_times(const r3_ctx* ctx, float* out, uint32_t cap, uint32_t* n_out) {
+  if (ctx == nullptr || n_out == nullptr || (cap && out == nullptr)) return R3_EINVAL;
+  *n_out = (uint32_t)ctx->last_times.size();
+  for (uint32_t i = 0; i < cap && i < ctx->last_times.size(); ++i) out[i] = ctx->last_times[i];
+  return R3_OK;
 }
 
 }  // extern "C"

@@ -151,6 +151,7 @@ struct r3_ctx {
   r3::GuardSlot* guard_pinned = nullptr;      // R3_MAX_REPLAYS slots, pinned host memory
   r3::GuardSlot* guard_pinned_dev = nullptr;
   uint64_t seq = 0;                    // sequence number of the last validation enqueued
+  std::vector<float> last_times;       // candidate ms of the timed replays of the last evaluation
   uint32_t profile_period = 0;         // 0 = off, n = stage events on every n-th evaluation
   uint64_t evals = 0;
   std::vector<hipEvent_t> events;  // 4 per replay, grown on demand

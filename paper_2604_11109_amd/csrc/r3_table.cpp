@@ -189,6 +189,46 @@ int r3_writeset_regions(const uint64_t* host_bitmap, uint64_t bytes, uint32_t pa
   return runs > cap ? R3_ENOSPC : R3_OK;
 }
 
+int r3_table_replicate(const r3_region* host_tbl, uint32_t n, uint64_t instance_stride,
+                       uint32_t instances, r3_region* out) {
+  if (host_tbl == nullptr || out == nullptr || n == 0 || instances == 0) return R3_EINVAL;
+  if ((uint64_t)n * instances > 0xFFFFFFFFull) return R3_ERANGE;
+  for (uint32_t i = 0; i < instances; ++i)
+    for (uint32_t r = 0; r < n; ++r) {
+      r3_region g = host_tbl[r];
+      const uint64_t shift = (uint64_t)i * instance_stride;
+      if (g.offset > UINT64_MAX - shift) return R3_ERANGE;
+      g.offset += shift;
+      out[(size_t)i * n + r] = g;
+    }
+  return R3_OK;
+}
+
+int r3_timing_stats(const float* ms, uint32_t n, float rel_noise, r3_timing* out) {
+  if (out == nullptr || (n && ms == nullptr)) return R3_EINVAL;
+  *out = r3_timing{};
+  if (n == 0) return R3_OK;
+  std::vector<float> v(ms, ms + n);
+  std::sort(v.begin(), v.end());
+  auto median_of = [](const std::vector<float>& s) {
+    const size_t m = s.size();
+    return m % 2 ? s[m / 2] : 0.5f * (s[m / 2 - 1] + s[m / 2]);
+  };
+  out->n = n;
+  out->min = v.front();
+  out->max = v.back();
+  out->median = median_of(v);
+  double sum = 0;
+  for (float x : v) sum += x;
+  out->mean = (float)(sum / n);
+  std::vector<float> dev(n);
+  for (uint32_t i = 0; i < n; ++i) dev[i] = std::fabs(v[i] - out->median);
+  std::sort(dev.begin(), dev.end());
+  out->mad = median_of(dev);
+  out->stable = (out->median > 0 && out->mad <= rel_noise * out->median) ? 1u : 0u;
+  return R3_OK;
+}
+
 int r3_tune_tiles(uint32_t min_tile_bytes, uint32_t max_tiles_per_region) {
   auto log2_exact = [](uint32_t v) -> int {
     if (v == 0 || (v & (v - 1))) return -1;

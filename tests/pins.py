@@ -666,10 +666,52 @@ def check_eval_guard(api, seed=20):
     assert live2[12 * P + 1] != pro[12 * P + 1]
 
 
+def check_instances(api, seed=21):
+    rng = np.random.default_rng(seed)
+    n, k, stride = 512, 3, 1024            # three recorded instances, 1 KiB apart
+    pro = rng.integers(0, 256, size=k * stride, dtype=np.uint8)
+    def kernel(view, i):                   # out = in + 1 (second half of each instance)
+        view[256:512] = view[0:256] + 1
+        return 0
+    epi = pro.copy()
+    for i in range(k):
+        kernel(epi[i * stride:], i)
+    one = api.make_table([(0, 256, api.U8, 0, 0, 0), (256, 256, api.U8, 0, 0, 0)])
+    rep = api.replicate_table(one, stride, k)
+    assert [(int(r["offset"]), int(r["bytes"])) for r in rep] == [
+        (0, 256), (256, 256), (1024, 256), (1280, 256), (2048, 256), (2304, 256)]
+    assert api.validate_table(rep, k * stride) == api.OK
+    live = np.zeros(k * stride, np.uint8)
+    out = api.eval_candidate_instances(rep, pro, rep, epi, live, kernel, k, stride, 1, 2)
+    assert out["pass"] == 1 and list(out["instance_pass"]) == [1, 1, 1]
+    # a candidate that is right on the recording used during the search and wrong on another
+    def partial(view, i):
+        kernel(view, i)
+        if i == 2:
+            view[300] ^= 8
+        return 0
+    out = api.eval_candidate_instances(rep, pro, rep, epi, live, partial, k, stride, 0, 2)
+    assert out["pass"] == 0 and list(out["instance_pass"]) == [1, 1, 0]
+    assert out["total_mismatch"] == 1 and out["first_region"] == 5 and out["first_index"] == 300 - 256
+    # bytes between the instances are never touched
+    assert (live[512:1024] == 0).all() and (live[1536:2048] == 0).all()
+
+
+def check_timing_stats(api):
+    t = api.timing_stats([3.0, 1.0, 2.0, 10.0, 2.5], 0.5)
+    assert (t["n"], t["min"], t["median"], t["max"]) == (5, 1.0, 2.5, 10.0) and abs(t["mean"] - 3.7) < 1e-6
+    assert t["mad"] == 0.5 and t["stable"] == 1          # |x - 2.5| = .5 1.5 .5 7.5 0 -> median .5
+    assert api.timing_stats([3.0, 1.0, 2.0, 10.0, 2.5], 0.1)["stable"] == 0
+    t = api.timing_stats([4.0, 2.0], 0.0)
+    assert t["median"] == 3.0 and t["mad"] == 1.0 and t["stable"] == 0
+    assert api.timing_stats([7.0], 0.0)["stable"] == 1 and api.timing_stats([], 1.0)["n"] == 0
+
+
 ALL_CHECKS = [
     check_checksum_constants, check_checksum_golden, check_checksum_bruteforce,
     check_checksum_properties, check_checksum_table, check_compare_bruteforce,
     check_compare_worked_example, check_compare_isclose, check_compare_closed_forms,
     check_compare_unfused, check_summary, check_restore, check_dirty_diff, check_table_rules,
     check_eval_loop, check_record, check_writeset_regions, check_eval_guard,
+    check_instances, check_timing_stats,
 ]

@@ -123,3 +123,23 @@ def test_writeset_regions_agree_with_oracle(r3, oracle):
                 b = oracle.writeset_regions(bm, nbytes, page, want)
                 assert a.tobytes() == b.tobytes(), (nbytes, page, density, want)
     assert len(r3.r3_writeset_regions(np.zeros(0, np.uint64), 0, 4096, 1)) == 0
+
+
+def test_replicate_and_timing_agree_with_oracle(r3, oracle):
+    rows = [(0, 64, 1, 1, 1e-5, 1e-7), (64, 32, 4, 0, 0, 0), (128, 0, 2, 0, 0, 0)]
+    a = r3.r3_table_replicate(r3.make_table(rows), 4096, 5)
+    b = oracle.replicate_table(oracle.make_table(rows), 4096, 5)
+    assert a.tobytes() == b.tobytes()
+    with pytest.raises(r3.R3Error):
+        r3.r3_table_replicate(r3.make_table([(2**63, 8, 2, 0, 0, 0)]), 2**63, 3)
+    rng = np.random.default_rng(9)
+    for n in [0, 1, 2, 3, 4, 7, 10, 33]:
+        ms = (rng.random(n) * 3 + 0.1).astype(np.float32)
+        for tol in (0.0, 0.05, 0.5):
+            t = r3.r3_timing_stats(ms, tol)
+            e = oracle.timing_stats(ms, tol)
+            assert (t.n, t.stable) == (e["n"], e["stable"])
+            got = np.array([t.min, t.median, t.max, t.mad], dtype=np.float32)
+            exp = np.array([e["min"], e["median"], e["max"], e["mad"]], dtype=np.float32)
+            assert (got == exp).all(), (n, tol, got, exp)
+            assert abs(t.mean - e["mean"]) <= 1e-6 * max(1.0, abs(e["mean"]))
