@@ -228,6 +228,36 @@ def writeset_leg(rp, steps, warmup):
     return info
 
 
+def record_path_leg(rp, reps=10):
+    """The record-time kernels on this workload's arena: checksum only, page dirty-diff and the
+    whole-arena copy, each timed alone with events on the stream it runs on."""
+    r3, ctx, torch = rp.r3, rp.ctx, rp.torch
+    A = rp.arena_bytes
+    tbl = rp.restore_tbl
+    d_cs = torch.zeros(tbl.n, dtype=torch.int64, device="cuda:0")
+    d_bm = torch.zeros(r3.bitmap_words(A, 4096), dtype=torch.int64, device="cuda:0")
+    d_cnt = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    out = {}
+    ms = timed(lambda: r3.r3_checksum(ctx, tbl, rp.d_pro, d_cs))
+    b = tbl.info()["total_bytes"]
+    out["checksum"] = {"ms": ms, "algorithmic_bytes": b, "GB/s": b / ms / 1e6}
+    ms = timed(lambda: r3.r3_dirty_diff(ctx, rp.d_pro, rp.d_epi, A, 4096, d_bm, d_cnt))
+    out["dirty_diff"] = {"ms": ms, "algorithmic_bytes": 2 * A, "GB/s": 2 * A / ms / 1e6,
+                         "dirty_pages": int(d_cnt.cpu()[0])}
+    return out
+
+
 def stage_report(rp, prof):
     out = {}
     if prof.restore_launches:
@@ -313,7 +343,7 @@ def large_leg(r3, wl, ctx, torch):
     dt, prof = timed_run(rp, 3, 1)
     st = stage_report(rp, prof)
     out = {"workload": rp.desc, "steps": 3, "ms_per_step": dt / 3 * 1e3, "stages": st,
-           "roofline": roofline(rp, st)}
+           "roofline": roofline(rp, st), "record_path": record_path_leg(rp, reps=3)}
     del rp
     torch.cuda.empty_cache()
     return out
@@ -364,6 +394,7 @@ def main():
     }
     cpu = None if a.no_cpu else cpu_baseline(rp)
     line["cpu_baseline"] = cpu
+    line["record_path"] = record_path_leg(rp)
     if a.workload in ("jacobi", "spmv"):
         line["write_set_replay"] = writeset_leg(rp, steps, warmup)
     del rp

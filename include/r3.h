@@ -345,6 +345,31 @@ int r3_eval_candidate_instances(r3_ctx* ctx, const r3_table* restore_tbl, const 
                                 uint32_t compare_policy, r3_region_result* d_regions,
                                 r3_eval_result* host_out, uint8_t* host_instance_pass, void* stream);
 
+/* ---- a replay captured as a HIP graph ----------------------------------- */
+
+/* For evaluations bound by launch latency (small states, many replays): the whole
+ * evaluation -- `replays` times restore, the candidate's launches, validation -- is recorded
+ * once as a HIP graph and then launched as a unit.  The candidate is timed by wall-clock
+ * stamps taken on the device before and after it (their difference includes the dispatch
+ * gap of the candidate).
+ *
+ * r3_replay_create records the graph; the launch callback is called `replays` times, on an
+ * internal capture stream, and must only enqueue kernels on the stream it is given.  d_ws:
+ * device, r3_replay_workspace_bytes() bytes, 16-byte aligned, owned by the caller until
+ * r3_replay_destroy; all other pointers as in r3_eval_candidate and equally long-lived.
+ * r3_replay_run launches the graph once on `stream` (warmup + reps must equal `replays`),
+ * waits, and fills host_out like r3_eval_candidate with policy R3_POLICY_EVERY (d_regions
+ * holds the last replay).  One run at a time per replay object. */
+typedef struct r3_replay r3_replay;
+size_t r3_replay_workspace_bytes(void);
+int r3_replay_create(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
+                     const r3_table* check_tbl, const void* d_epilogue, void* d_live,
+                     r3_launch_fn launch, void* user, r3_region_result* d_regions, void* d_ws,
+                     uint32_t replays, r3_replay** out);
+int r3_replay_run(r3_replay* rp, uint32_t warmup, uint32_t reps, r3_eval_result* host_out,
+                  void* stream);
+int r3_replay_destroy(r3_replay* rp);
+
 /* ---- timing statistics -------------------------------------------------- */
 
 /* Candidate times (ms) of the timed replays of the last evaluation on ctx, in replay order:

@@ -74,6 +74,7 @@ DECLARED = [
     "r3_checksum", "r3_compare", "r3_dirty_diff", "r3_record", "r3_eval_candidate",
     "r3_writeset_regions", "r3_eval_candidate_guarded", "r3_table_replicate",
     "r3_eval_candidate_instances", "r3_ctx_last_times", "r3_timing_stats",
+    "r3_replay_workspace_bytes", "r3_replay_create", "r3_replay_run", "r3_replay_destroy",
 ]
 
 _lib = None
@@ -131,6 +132,10 @@ def lib():
                                                   vp, ctypes.POINTER(EvalResult), vp, vp]
         L.r3_ctx_last_times.argtypes = [vp, vp, u32, ctypes.POINTER(u32)]
         L.r3_timing_stats.argtypes = [vp, u32, ctypes.c_float, ctypes.POINTER(Timing)]
+        L.r3_replay_workspace_bytes.restype = sz
+        L.r3_replay_create.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, ctypes.POINTER(vp)]
+        L.r3_replay_run.argtypes = [vp, u32, u32, ctypes.POINTER(EvalResult), vp]
+        L.r3_replay_destroy.argtypes = [vp]
         for name in DECLARED:
             getattr(L, name)  # AttributeError if the library does not export it
         _lib = L
@@ -458,6 +463,46 @@ def r3_eval_candidate_instances(ctx, restore_tbl, d_prologues, check_tbl, d_epil
     if rc != ECANDIDATE:
         ctx.check(rc, "r3_eval_candidate_instances")
     return rc, out, flags
+
+
+class Replay:
+    """r3_replay: one replay captured as a HIP graph, plus the tensors it refers to."""
+
+    def __init__(self, ctx, restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, launch, user, d_regions,
+                 replays):
+        import torch
+        _need(d_prologue, restore_tbl.arena_bytes, "prologue")
+        _need(d_epilogue, check_tbl.arena_bytes, "epilogue")
+        _need(d_live, max(restore_tbl.arena_bytes, check_tbl.arena_bytes), "live arena")
+        _need(d_regions, 40 * check_tbl.n, "region results")
+        self.ctx = ctx
+        self.keep = (restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, user, d_regions)
+        self.workspace = torch.zeros(int(lib().r3_replay_workspace_bytes()), dtype=torch.uint8,
+                                     device="cuda:%d" % ctx.device)
+        fn, usr, self.keep_fn = _launch_args(launch, user)
+        h = ctypes.c_void_p()
+        rc = lib().r3_replay_create(ctx.handle, restore_tbl.handle, _ptr(d_prologue), check_tbl.handle,
+                                    _ptr(d_epilogue), _ptr(d_live), fn, _ptr(usr), _ptr(d_regions),
+                                    self.workspace.data_ptr(), replays, ctypes.byref(h))
+        ctx.check(rc, "r3_replay_create")
+        self.handle = h
+
+    def run(self, warmup, reps, stream=None):
+        out = EvalResult()
+        self.ctx.check(lib().r3_replay_run(self.handle, warmup, reps, ctypes.byref(out), _stream(stream)),
+                       "r3_replay_run")
+        return out
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib().r3_replay_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def r3_timing_stats(ms, rel_noise):

@@ -236,7 +236,7 @@ int r3_compare(r3_ctx* ctx, const r3_table* tbl, const void* d_live, const void*
     return fail(ctx, R3_EINVAL, "pointer is NULL");
   if (!aligned16(d_live) || !aligned16(d_golden)) return fail(ctx, R3_EALIGN, "arena base not 16-byte aligned");
   DeviceGuard guard(ctx->device);
-  hipError_t e = r3::launch_compare(tbl->dev, d_live, d_golden, d_out, d_summary, nullptr, 0,
+  hipError_t e = r3::launch_compare(tbl->dev, d_live, d_golden, d_out, d_summary, nullptr, 0, nullptr,
                                     as_stream(stream));
   return e == hipSuccess ? R3_OK : fail_hip(ctx, e, "compare launch");
 }
@@ -376,7 +376,7 @@ static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pro
                           (compare_policy == R3_POLICY_LAST && rep == total - 1);
     if (validate) {
       e = r3::launch_compare(check_tbl->dev, d_live, d_epilogue, d_regions, nullptr,
-                             &ctx->pinned_dev[n_validated], ++ctx->seq, s);
+                             &ctx->pinned_dev[n_validated], ++ctx->seq, nullptr, s);
       last_flag = &ctx->pinned[n_validated].seq;
       last_want = ctx->seq;
       if (e != hipSuccess) break;
@@ -544,6 +544,146 @@ int r3_eval_candidate_instances(r3_ctx* ctx, const r3_table* restore_tbl, const 
     }
   }
   return rc;
+}
+
+size_t r3_replay_workspace_bytes(void) { return 256; }
+
+int r3_replay_destroy(r3_replay* rp) {
+  if (rp == nullptr) return R3_EINVAL;
+  DeviceGuard device_guard(rp->ctx->device);
+  if (rp->exec) (void)hipGraphExecDestroy(rp->exec);
+  if (rp->graph) (void)hipGraphDestroy(rp->graph);
+  if (rp->capture_stream) (void)hipStreamDestroy(rp->capture_stream);
+  if (rp->slots) (void)hipHostFree(rp->slots);
+  if (rp->stamps) (void)hipHostFree(rp->stamps);
+  delete rp;
+  return R3_OK;
+}
+
+int r3_replay_create(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
+                     const r3_table* check_tbl, const void* d_epilogue, void* d_live,
+                     r3_launch_fn launch, void* user, r3_region_result* d_regions, void* d_ws,
+                     uint32_t replays, r3_replay** out) {
+  int rc = check_common(ctx, restore_tbl);
+  if (rc == R3_OK) rc = check_common(ctx, check_tbl);
+  if (rc != R3_OK) return rc;
+  if (out == nullptr || d_prologue == nullptr || d_epilogue == nullptr || d_live == nullptr ||
+      d_regions == nullptr || d_ws == nullptr)
+    return fail(ctx, R3_EINVAL, "pointer is NULL");
+  *out = nullptr;
+  if (!aligned16(d_prologue) || !aligned16(d_epilogue) || !aligned16(d_live) || !aligned16(d_ws))
+    return fail(ctx, R3_EALIGN, "pointer not 16-byte aligned");
+  if (replays == 0 || replays > R3_MAX_REPLAYS) return fail(ctx, R3_EINVAL, "replays must be 1..R3_MAX_REPLAYS");
+  DeviceGuard device_guard(ctx->device);
+  r3_replay* rp = new (std::nothrow) r3_replay();
+  if (rp == nullptr) return fail(ctx, R3_ENOSPC, "out of host memory");
+  rp->ctx = ctx;
+  rp->check_tbl = check_tbl;
+  rp->d_counter = static_cast<uint32_t*>(d_ws);
+  rp->has_candidate = launch != nullptr;
+  int khz = 0;
+  hipError_t e = hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, ctx->device);
+  if (e == hipSuccess && khz <= 0) e = hipErrorInvalidValue;
+  rp->ticks_per_ms = (double)khz;
+  if (e == hipSuccess)
+    e = hipHostMalloc(reinterpret_cast<void**>(&rp->slots), R3_MAX_REPLAYS * sizeof(r3::HostSlot),
+                      hipHostMallocMapped);
+  if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void**>(&rp->slots_dev), rp->slots, 0);
+  if (e == hipSuccess)
+    e = hipHostMalloc(reinterpret_cast<void**>(&rp->stamps), R3_MAX_REPLAYS * 2 * sizeof(uint64_t),
+                      hipHostMallocMapped);
+  if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void**>(&rp->stamps_dev), rp->stamps, 0);
+  if (e == hipSuccess) {
+    std::memset(rp->slots, 0, R3_MAX_REPLAYS * sizeof(r3::HostSlot));
+    e = hipStreamCreateWithFlags(&rp->capture_stream, hipStreamNonBlocking);
+  }
+  if (e != hipSuccess) {
+    (void)r3_replay_destroy(rp);
+    return fail_hip(ctx, e, "replay set-up");
+  }
+  // Record the replay: nothing below executes now, the launches become graph nodes.
+  hipStream_t cs = rp->capture_stream;
+  e = hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal);
+  int cand = 0;
+  if (e == hipSuccess) {
+    hipError_t ce = hipSuccess;
+    for (uint32_t r = 0; r < replays && ce == hipSuccess && cand == 0; ++r) {
+      ce = r3::launch_restore(restore_tbl->dev, restore_tbl->class_count, d_prologue, d_live, cs);
+      // stamp 0 also advances the replay counter, so it is always there
+      if (ce == hipSuccess) ce = r3::launch_stamp(rp->d_counter, rp->stamps_dev, 0, cs);
+      if (ce == hipSuccess && launch) {
+        cand = launch(user, d_live, cs);
+        hipError_t le = hipGetLastError();
+        if (cand == 0 && le != hipSuccess) cand = -(int)le;
+        if (cand == 0) ce = r3::launch_stamp(rp->d_counter, rp->stamps_dev, 1, cs);
+      }
+      if (ce == hipSuccess && cand == 0)
+        ce = r3::launch_compare(check_tbl->dev, d_live, d_epilogue, d_regions, nullptr, rp->slots_dev, 1,
+                                rp->d_counter, cs);
+    }
+    hipError_t ee = hipStreamEndCapture(cs, &rp->graph);
+    e = ce != hipSuccess ? ce : ee;
+  }
+  rp->replays = replays;
+  if (e == hipSuccess && cand == 0) e = hipGraphInstantiate(&rp->exec, rp->graph, nullptr, nullptr, 0);
+  if (cand != 0) {
+    (void)r3_replay_destroy(rp);
+    return fail(ctx, R3_ECANDIDATE, "the candidate failed to launch during capture");
+  }
+  if (e != hipSuccess) {
+    (void)r3_replay_destroy(rp);
+    return fail_hip(ctx, e, "replay capture");
+  }
+  *out = rp;
+  return R3_OK;
+}
+
+int r3_replay_run(r3_replay* rp, uint32_t warmup, uint32_t reps, r3_eval_result* host_out, void* stream) {
+  if (rp == nullptr || host_out == nullptr) return R3_EINVAL;
+  r3_ctx* ctx = rp->ctx;
+  ctx->err.clear();
+  const uint64_t total = (uint64_t)warmup + reps;
+  if (reps == 0) return fail(ctx, R3_EINVAL, "reps must be at least 1");
+  if (total != rp->replays) return fail(ctx, R3_EINVAL, "warmup + reps differs from the captured replay count");
+  DeviceGuard device_guard(ctx->device);
+  hipStream_t s = as_stream(stream);
+  std::memset(host_out, 0, sizeof(*host_out));
+  host_out->first_index = R3_NO_INDEX;
+  host_out->first_region = R3_NO_REGION;
+  for (uint64_t i = 0; i < total; ++i) rp->slots[i].seq = 0;
+  hipError_t e = r3::launch_set_counter(rp->d_counter, 0, s);
+  if (e == hipSuccess) e = hipGraphLaunch(rp->exec, s);
+  bool arrived = false;
+  if (e == hipSuccess) {
+    const uint64_t want = total;  // replay k posts sequence number k + 1
+    for (uint32_t spin = 0; spin < (1u << 22) && !arrived; ++spin)
+      arrived = __atomic_load_n(&rp->slots[total - 1].seq, __ATOMIC_ACQUIRE) == want;
+  }
+  if (!arrived) {
+    hipError_t we = hipStreamSynchronize(s);
+    if (e == hipSuccess) e = we;
+  }
+  if (e != hipSuccess) return fail_hip(ctx, e, "captured replay");
+  for (uint64_t i = 0; i < total; ++i)
+    host_out->total_mismatch = std::max(host_out->total_mismatch, rp->slots[i].summary.total_mismatch);
+  const r3_summary& last = rp->slots[total - 1].summary;
+  host_out->first_index = last.first_index;
+  host_out->first_region = last.first_region;
+  host_out->max_abs_err = last.max_abs_err;
+  host_out->max_rel_err = last.max_rel_err;
+  host_out->pass = host_out->total_mismatch == 0 ? 1u : 0u;
+  ctx->last_times.clear();
+  if (rp->has_candidate) {
+    std::vector<float> ms;
+    for (uint64_t i = warmup; i < total; ++i)
+      ms.push_back((float)((double)(rp->stamps[2 * i + 1] - rp->stamps[2 * i]) / rp->ticks_per_ms));
+    ctx->last_times = ms;
+    std::sort(ms.begin(), ms.end());
+    host_out->ms_min = ms.front();
+    host_out->ms_max = ms.back();
+    host_out->ms_median = ms.size() % 2 ? ms[ms.size() / 2] : 0.5f * (ms[ms.size() / 2 - 1] + ms[ms.size() / 2]);
+  }
+  return R3_OK;
 }
 
 int r3_ctx_last_times(const r3_ctx* ctx, float* out, uint32_t cap, uint32_t* n_out) {

@@ -135,7 +135,9 @@ hipError_t launch_copy_flat(const void* src, void* dst, uint64_t bytes, hipStrea
 hipError_t launch_checksum(const TableDev& t, const void* arena, uint64_t* out, hipStream_t s);
 hipError_t launch_compare(const TableDev& t, const void* live, const void* golden,
                           r3_region_result* out, r3_summary* summary, HostSlot* host_slot,
-                          uint64_t host_seq, hipStream_t s);
+                          uint64_t host_seq, const uint32_t* rep_counter, hipStream_t s);
+hipError_t launch_stamp(uint32_t* rep_counter, uint64_t* stamps, uint32_t which, hipStream_t s);
+hipError_t launch_set_counter(uint32_t* rep_counter, uint32_t value, hipStream_t s);
 hipError_t launch_guard_compare(const uint64_t* got, const uint64_t* expected, uint32_t n,
                                 GuardSlot* host_slot, uint64_t host_seq, hipStream_t s);
 hipError_t launch_dirty_diff(const void* pre, const void* post, uint64_t bytes, uint32_t page_bytes,
@@ -164,4 +166,21 @@ struct r3_table {
   uint64_t arena_bytes = 0;
   uint64_t total_bytes = 0;
   uint32_t class_count[r3::kMaxCopyClasses] = {};
+};
+
+// One replay (restore, candidate, validation) captured as a HIP graph.
+struct r3_replay {
+  r3_ctx* ctx = nullptr;
+  const r3_table* check_tbl = nullptr;
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+  hipStream_t capture_stream = nullptr;
+  uint32_t* d_counter = nullptr;            // in the caller's workspace
+  r3::HostSlot* slots = nullptr;            // pinned: one verdict per replay
+  r3::HostSlot* slots_dev = nullptr;
+  uint64_t* stamps = nullptr;               // pinned: start/end wall clock per replay
+  uint64_t* stamps_dev = nullptr;
+  double ticks_per_ms = 0;
+  bool has_candidate = false;
+  uint32_t replays = 0;                     // replays recorded in the graph
 };

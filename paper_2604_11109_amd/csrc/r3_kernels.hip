@@ -762,7 +762,8 @@ __device__ __forceinline__ void write_summary(r3_summary* dst, uint64_t total, u
 template <int BLOCK>
 __global__ __launch_bounds__(BLOCK) void compare_finalize_kernel(TableDev t, r3_region_result* out,
                                                                  r3_summary* summary,
-                                                                 HostSlot* host_slot, uint64_t host_seq) {
+                                                                 HostSlot* host_slot, uint64_t host_seq,
+                                                                 const uint32_t* rep_counter) {
   constexpr int NW = BLOCK / 64;
   constexpr int kAhead = 4;  // partials fetched per thread before any is folded
   __shared__ uint64_t sh[5][NW];
@@ -833,8 +834,10 @@ __global__ __launch_bounds__(BLOCK) void compare_finalize_kernel(TableDev t, r3_
     const uint64_t fi = f.count ? f.first : R3_NO_INDEX;
     if (summary) write_summary(summary, f.count, fr, fi, f.max_abs, f.max_rel);
     if (host_slot) {
-      write_summary(&host_slot->summary, f.count, fr, fi, f.max_abs, f.max_rel);
-      publish_seq(host_slot, host_seq);
+      // inside a captured replay the slot and sequence number advance with the replay count
+      const uint32_t k = rep_counter ? *rep_counter - 1 : 0;
+      write_summary(&host_slot[k].summary, f.count, fr, fi, f.max_abs, f.max_rel);
+      publish_seq(host_slot + k, host_seq + k);
     }
   }
 }
@@ -842,7 +845,7 @@ __global__ __launch_bounds__(BLOCK) void compare_finalize_kernel(TableDev t, r3_
 // Table verdict from the per-region results (one block; runs after the finalize launch).
 __global__ __launch_bounds__(kBlock) void summary_kernel(const r3_region_result* out, uint32_t n,
                                                          r3_summary* summary, HostSlot* host_slot,
-                                                         uint64_t host_seq) {
+                                                         uint64_t host_seq, const uint32_t* rep_counter) {
   __shared__ uint64_t sh[3][kWavesPerBlock];
   __shared__ uint32_t sh_first_region[kWavesPerBlock];
   const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -876,8 +879,9 @@ __global__ __launch_bounds__(kBlock) void summary_kernel(const r3_region_result*
     const uint64_t first_index = first_region == R3_NO_REGION ? R3_NO_INDEX : out[first_region].first_mismatch;
     if (summary) write_summary(summary, total, first_region, first_index, max_abs, max_rel);
     if (host_slot) {
-      write_summary(&host_slot->summary, total, first_region, first_index, max_abs, max_rel);
-      publish_seq(host_slot, host_seq);
+      const uint32_t k = rep_counter ? *rep_counter - 1 : 0;
+      write_summary(&host_slot[k].summary, total, first_region, first_index, max_abs, max_rel);
+      publish_seq(host_slot + k, host_seq + k);
     }
   }
 }
@@ -985,6 +989,26 @@ __global__ __launch_bounds__(kBlock) void guard_compare_kernel(const uint64_t* g
   }
 }
 
+// Time stamps around the candidate inside a captured replay.  `which` 0: take the next replay
+// number (the counter advances) and stamp its start; 1: stamp its end.  The stamps go to
+// pinned host memory, the counter lives in device memory.
+__global__ void stamp_kernel(uint32_t* rep_counter, uint64_t* stamps, uint32_t which) {
+  if (threadIdx.x == 0) {
+    uint32_t k;
+    if (which == 0) {
+      k = *rep_counter;
+      *rep_counter = k + 1;
+    } else {
+      k = *rep_counter - 1;
+    }
+    stamps[2 * k + which] = wall_clock64();
+  }
+}
+
+__global__ void set_counter_kernel(uint32_t* rep_counter, uint32_t value) {
+  if (threadIdx.x == 0) *rep_counter = value;
+}
+
 uint32_t grid_for(uint64_t tiles) { return (uint32_t)((tiles + kWavesPerBlock - 1) / kWavesPerBlock); }
 
 }  // namespace
@@ -1065,7 +1089,7 @@ hipError_t launch_checksum(const TableDev& t, const void* arena, uint64_t* out, 
 
 hipError_t launch_compare(const TableDev& t, const void* live, const void* golden,
                           r3_region_result* out, r3_summary* summary, HostSlot* host_slot,
-                          uint64_t host_seq, hipStream_t s) {
+                          uint64_t host_seq, const uint32_t* rep_counter, hipStream_t s) {
   if (t.n_tiles) {
     compare_kernel<<<grid_for(t.n_tiles), kBlock, 0, s>>>(t, (const uint8_t*)live,
                                                           (const uint8_t*)golden);
@@ -1074,21 +1098,31 @@ hipError_t launch_compare(const TableDev& t, const void* live, const void* golde
   }
   switch (finalize_block(t.max_region_tiles)) {
     case 64:
-      compare_finalize_kernel<64><<<t.n_regions, 64, 0, s>>>(t, out, summary, host_slot, host_seq);
+      compare_finalize_kernel<64><<<t.n_regions, 64, 0, s>>>(t, out, summary, host_slot, host_seq, rep_counter);
       break;
     case 256:
-      compare_finalize_kernel<256><<<t.n_regions, 256, 0, s>>>(t, out, summary, host_slot, host_seq);
+      compare_finalize_kernel<256><<<t.n_regions, 256, 0, s>>>(t, out, summary, host_slot, host_seq, rep_counter);
       break;
     default:
-      compare_finalize_kernel<1024><<<t.n_regions, 1024, 0, s>>>(t, out, summary, host_slot, host_seq);
+      compare_finalize_kernel<1024><<<t.n_regions, 1024, 0, s>>>(t, out, summary, host_slot, host_seq, rep_counter);
       break;
   }
   hipError_t e = hipGetLastError();
   if (e == hipSuccess && t.n_regions > 1 && (summary != nullptr || host_slot != nullptr)) {
-    summary_kernel<<<1, kBlock, 0, s>>>(out, t.n_regions, summary, host_slot, host_seq);
+    summary_kernel<<<1, kBlock, 0, s>>>(out, t.n_regions, summary, host_slot, host_seq, rep_counter);
     e = hipGetLastError();
   }
   return e;
+}
+
+hipError_t launch_stamp(uint32_t* rep_counter, uint64_t* stamps, uint32_t which, hipStream_t s) {
+  stamp_kernel<<<1, 64, 0, s>>>(rep_counter, stamps, which);
+  return hipGetLastError();
+}
+
+hipError_t launch_set_counter(uint32_t* rep_counter, uint32_t value, hipStream_t s) {
+  set_counter_kernel<<<1, 64, 0, s>>>(rep_counter, value);
+  return hipGetLastError();
 }
 
 hipError_t launch_guard_compare(const uint64_t* got, const uint64_t* expected, uint32_t n,
