@@ -108,6 +108,7 @@ class Replay:
             self.d_epi = self.d_pro
             self.d_live = up(c["live"])
             self.expect_pass = [True]
+            self.host_case = c
             self.desc = "4096 regions 256 B..1 MiB (fp32/fp64/int32/bf16), %.0f MiB, restore + validate" % (A / 2**20)
         elif name == "large_snapshot":
             c = ri.large_snapshot_device()
@@ -132,6 +133,7 @@ class Replay:
             self.candidates = [wl.spmv_args(c, r, b) for r, b in ri.SPMV_VARIANTS]
             self.baseline_index = ri.SPMV_VARIANTS.index((64, 256))
             self.expect_pass = [True if r >= 64 else None for r, _ in ri.SPMV_VARIANTS]
+            self.host_case = c
             self.desc = "CSR SpMV 2^21 rows x 27 nnz fp64, 64 launch configurations, full-arena restore 688 MiB"
         self.arena_bytes = A
         self.d_regions = torch.zeros(40 * self.check_tbl.n, dtype=torch.uint8, device="cuda:0")
@@ -331,7 +333,57 @@ def cpu_baseline(rp):
         dt = time.perf_counter() - t0
         return {"value": evals / dt, "unit": "evals/s", "cores": 1, "kind": "oracle",
                 "sample": "%d pure restore->validate replays at full size" % evals}
-    # generic: restore + compare of a 256 MiB slice of the first regions, scaled by bytes
+    if rp.name == "many_regions":
+        c = rp.host_case
+        t = o.make_table(c["rows"])
+        live = c["live"].copy()
+        evals, t0 = 0, time.perf_counter()
+        while evals < 4 and (evals == 0 or time.perf_counter() - t0 < 12.0):
+            res = o.eval_candidate(t, c["snapshot"], t, c["snapshot"], live, None, 0, 1)
+            evals += 1
+        dt = time.perf_counter() - t0
+        assert res["pass"] == 1
+        return {"value": evals / dt, "unit": "evals/s", "cores": 1, "kind": "oracle",
+                "sample": "%d restore->validate replays of all 4096 regions" % evals}
+    if rp.name == "spmv":
+        c = rp.host_case
+        rows = c["rows"]
+        row_ptr, col, vals, x = c["csr"]
+        y_off, y_bytes = c["offsets"]["y"], c["sizes"]["y"]
+        rt, ct = o.make_table(c["table_rows"]), o.make_table(c["y_rows"])
+        epi = rp.d_epi.cpu().numpy()
+        live = np.zeros_like(c["prologue"])
+
+        def product(a):
+            y = (vals.reshape(rows, 27) * x[col]).sum(axis=1)
+            a[y_off:y_off + y_bytes] = y.astype("<f8").view(np.uint8)
+            return 0
+        evals, t0 = 0, time.perf_counter()
+        while evals < 4 and (evals == 0 or time.perf_counter() - t0 < 12.0):
+            o.eval_candidate(rt, c["prologue"], ct, epi, live, product, 0, 1)
+            evals += 1
+        dt = time.perf_counter() - t0
+        return {"value": evals / dt, "unit": "evals/s", "cores": 1, "kind": "oracle",
+                "sample": "%d evaluations: oracle restore of the 688 MiB arena, numpy row sums as the "
+                          "candidate, oracle compare of y (16 MiB)" % evals}
+    if rp.name == "large_snapshot":
+        # one fp32 and one bf16 region (2 of 16, 1/8 of the bytes), downloaded from the device
+        vals = []
+        for r in (0, 8):
+            off, nb = rp.check_tbl.host[r]["offset"], rp.check_tbl.host[r]["bytes"]
+            off, nb = int(off), int(nb)
+            snap = rp.d_pro[off:off + nb].cpu().numpy()
+            gold = rp.d_epi[off:off + nb].cpu().numpy()
+            live = np.empty_like(snap)
+            row = o.make_table([(0, nb) + tuple(rp.check_tbl.host[r].tolist()[2:])])
+            t0 = time.perf_counter()
+            o.eval_candidate(row, snap, row, gold, live, None, 0, 1)
+            vals.append(time.perf_counter() - t0)
+            del snap, gold, live
+        per_eval = sum(vals) * 8.0
+        return {"value": 1.0 / per_eval, "unit": "evals/s", "cores": 1, "kind": "oracle",
+                "sample": "restore+validate of regions 0 (fp32) and 8 (bf16), 4 GiB of the 32 GiB state; "
+                          "time scaled by 8 to the whole state"}
     return None
 
 
