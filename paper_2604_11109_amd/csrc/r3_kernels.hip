@@ -231,15 +231,22 @@ __device__ __forceinline__ uint32_t elem_size_dev(uint32_t dtype) {
 // 5.1-5.4 TB/s for wavefronts that walk 64 KiB or more.  A table tile is therefore spread
 // over 2^sub_log2 consecutive wavefront slots; slots past the end of a tile exit at once.
 template <int BLOCK>
-__global__ __launch_bounds__(BLOCK) void restore_kernel(TableDev t, CopyClasses cls, const uint8_t* src,
-                                                        uint8_t* dst, uint32_t copy_shift) {
+__global__ __launch_bounds__(BLOCK) void restore_kernel(TableDev t, const uint8_t* src, uint8_t* dst,
+                                                        uint32_t copy_shift, uint32_t n_classes,
+                                                        uint32_t sub_log2_0, uint64_t total_slots,
+                                                        CopyClasses cls) {
   const uint64_t slot = (uint64_t)blockIdx.x * (BLOCK / 64) + wave_in_block();
-  if (slot >= cls.slot_base[cls.n]) return;
-  uint32_t c = 0;  // size class of this slot: a short scalar scan of the launch arguments
-  while (c + 1 < cls.n && slot >= cls.slot_base[c + 1]) ++c;
-  const uint64_t rel = slot - cls.slot_base[c];
-  const uint32_t sub_log2 = cls.sub_log2[c];
-  const CopyTile* ct = &t.copy_tiles[cls.first[c] + (rel >> sub_log2)];
+  if (slot >= total_slots) return;
+  uint64_t rel = slot;
+  uint32_t sub_log2 = sub_log2_0, first = 0;
+  if (n_classes > 1) {  // size class of this slot: a short scalar scan of the launch arguments
+    uint32_t c = 0;
+    while (c + 1 < n_classes && slot >= cls.slot_base[c + 1]) ++c;
+    rel = slot - cls.slot_base[c];
+    sub_log2 = cls.sub_log2[c];
+    first = cls.first[c];
+  }
+  const CopyTile* ct = &t.copy_tiles[first + (rel >> sub_log2)];
   const uint64_t tile_at = sgpr(ct->at);
   const uint32_t tile_len = sgpr(ct->len), es = sgpr(ct->es);
   const uint32_t sub = (uint32_t)(rel & ((1ull << sub_log2) - 1));
@@ -940,17 +947,25 @@ __global__ __launch_bounds__(kBlock) void dirty_diff_kernel(const uint8_t* pre, 
   if (lane == 0) bitmap16[slice] = (uint16_t)bits;
 }
 
-__global__ __launch_bounds__(kBlock) void popcount_kernel(const uint64_t* bitmap, uint64_t n_words,
-                                                          uint64_t* count) {
-  __shared__ uint64_t sh[kWavesPerBlock];
+__global__ __launch_bounds__(1024) void popcount_kernel(const uint64_t* bitmap, uint64_t n_words,
+                                                        uint64_t* count) {
+  __shared__ uint64_t sh[16];
   uint64_t acc = 0;
-  for (uint64_t i = threadIdx.x; i < n_words; i += kBlock) acc += __popcll(bitmap[i]);
+  for (uint64_t i = threadIdx.x; i < n_words; i += 1024 * 4) {  // four loads in flight
+    uint64_t v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint64_t idx = i + (uint64_t)u * 1024;
+      v[u] = idx < n_words ? bitmap[idx] : 0;
+    }
+    acc += __popcll(v[0]) + __popcll(v[1]) + __popcll(v[2]) + __popcll(v[3]);
+  }
   acc = wave_sum(acc);
   if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = acc;
   __syncthreads();
   if (threadIdx.x == 0) {
     acc = 0;
-    for (int w = 0; w < kWavesPerBlock; ++w) acc += sh[w];
+    for (int w = 0; w < 16; ++w) acc += sh[w];
     *count = acc;
   }
 }
@@ -1045,10 +1060,19 @@ hipError_t launch_restore(const TableDev& t, const uint32_t* class_count, const 
   if (blocks > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
   const uint8_t* a = (const uint8_t*)src;
   uint8_t* b = (uint8_t*)dst;
+  // a table with a single size class (the common case) is resolved from the plain arguments
+  uint32_t used = 0, only = 0;
+  for (uint32_t c = 0; c < cls.n; ++c)
+    if (class_count[c]) {
+      ++used;
+      only = c;
+    }
+  const uint32_t n_classes = used <= 1 ? 1 : cls.n;
+  const uint32_t sub0 = used <= 1 ? cls.sub_log2[only] : 0;
   switch (g_copy_block) {
-    case 64: restore_kernel<64><<<(uint32_t)blocks, 64, 0, s>>>(t, cls, a, b, cs); break;
-    case 128: restore_kernel<128><<<(uint32_t)blocks, 128, 0, s>>>(t, cls, a, b, cs); break;
-    default: restore_kernel<256><<<(uint32_t)blocks, 256, 0, s>>>(t, cls, a, b, cs); break;
+    case 64: restore_kernel<64><<<(uint32_t)blocks, 64, 0, s>>>(t, a, b, cs, n_classes, sub0, slots, cls); break;
+    case 128: restore_kernel<128><<<(uint32_t)blocks, 128, 0, s>>>(t, a, b, cs, n_classes, sub0, slots, cls); break;
+    default: restore_kernel<256><<<(uint32_t)blocks, 256, 0, s>>>(t, a, b, cs, n_classes, sub0, slots, cls); break;
   }
   return hipGetLastError();
 }
@@ -1145,7 +1169,7 @@ hipError_t launch_dirty_diff(const void* pre, const void* post, uint64_t bytes, 
     if (e != hipSuccess) return e;
   }
   if (dirty_count) {
-    popcount_kernel<<<1, kBlock, 0, s>>>(bitmap, n_words, dirty_count);
+    popcount_kernel<<<1, 1024, 0, s>>>(bitmap, n_words, dirty_count);
     return hipGetLastError();
   }
   return hipSuccess;

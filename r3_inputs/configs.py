@@ -34,7 +34,7 @@ def bf16_bits_to_f32(b):
 
 
 # --------------------------------------------------------------------------------------
-# configs[0]: one small snapshot, three fp32 inputs + one fp32 output
+# the small-replay workload: one small snapshot, three fp32 inputs + one fp32 output
 # --------------------------------------------------------------------------------------
 def replay_small(n=1 << 20, seed=SEEDS["replay_small"], frac=1e-3, scale=1e-3):
     """Three fp32 input regions and one fp32 output region of n elements each.
@@ -76,7 +76,7 @@ def replay_small(n=1 << 20, seed=SEEDS["replay_small"], frac=1e-3, scale=1e-3):
 
 
 # --------------------------------------------------------------------------------------
-# configs[1]: 7-point Jacobi on an N^3 fp64 grid
+# the Jacobi workload: 7-point Jacobi on an N^3 fp64 grid
 # --------------------------------------------------------------------------------------
 def jacobi(n=256, seed=SEEDS["jacobi"]):
     """Arena = `in` (N^3 fp64; interior uniform[0,1), boundary planes 0) then `out` (zeros)."""
@@ -109,13 +109,13 @@ def jacobi_reference(grid):
     return out
 
 
-# Candidate variants of configs[1]: (block, unroll, bug)
+# Candidate variants of the Jacobi workload: (block, unroll, bug)
 JACOBI_VARIANTS = [(64, 1, 0), (128, 1, 0), (256, 1, 0), (512, 1, 0), (1024, 1, 0), (256, 2, 0),
                    (256, 4, 0), (128, 2, 1)]
 
 
 # --------------------------------------------------------------------------------------
-# configs[2]: many small regions of mixed element types
+# the many-regions workload: many small regions of mixed element types
 # --------------------------------------------------------------------------------------
 def many_regions(n_regions=4096, min_bytes=256, max_bytes=1 << 20, seed=SEEDS["many_regions"],
                  align=256, gap_fill=0xA5):
@@ -140,7 +140,7 @@ def many_regions(n_regions=4096, min_bytes=256, max_bytes=1 << 20, seed=SEEDS["m
 
 
 # --------------------------------------------------------------------------------------
-# configs[3]: a few very large regions, fp32 and bf16
+# the large-snapshot workload: a few very large regions, fp32 and bf16
 # --------------------------------------------------------------------------------------
 LARGE_TOL = {F32: (1e-5, 1e-7), BF16: (1e-2, 1e-3)}
 
@@ -238,7 +238,7 @@ def large_snapshot_device(n_regions=16, region_bytes=2 << 30, seed=SEEDS["large_
 
 
 # --------------------------------------------------------------------------------------
-# configs[4]: CSR SpMV with a banded pattern
+# the SpMV workload: CSR SpMV with a banded pattern
 # --------------------------------------------------------------------------------------
 def spmv(rows=1 << 21, seed=SEEDS["spmv"]):
     """27 non-zeros per row in 7 bands around centres {0, +-s, +-16s, +-s^2} (s = cube root of
@@ -291,7 +291,7 @@ def spmv(rows=1 << 21, seed=SEEDS["spmv"]):
             "csr": (row_ptr, col, vals, x)}
 
 
-# Candidate launch configurations of configs[4]: rows per wavefront x block size
+# Candidate launch configurations of the SpMV workload: rows per wavefront x block size
 SPMV_VARIANTS = [(rpw, blk) for rpw in (1, 2, 4, 8, 16, 32, 64, 128)
                  for blk in (64, 128, 192, 256, 320, 384, 448, 512)]
 

@@ -1,6 +1,6 @@
 """GPU parity of the replay loop (r3_record, r3_eval_candidate) with real candidate kernels:
-Jacobi variants (configs[1]), CSR SpMV launch configurations (configs[4]), the small
-replay (configs[0]) and the large snapshot (configs[3]).  For kernels the GPU ran, the
+Jacobi variants (the Jacobi workload), CSR SpMV launch configurations (the SpMV workload), the small
+replay (the small-replay workload) and the large snapshot (the large-snapshot workload).  For kernels the GPU ran, the
 oracle validates the bytes the candidate actually wrote (downloaded live memory)."""
 import ctypes
 
@@ -56,7 +56,7 @@ def check_eval_against_oracle(r3, oracle, out, d_regions, check_rows, live_host,
 
 
 # ----------------------------------------------------------------------------------------
-# configs[1]: Jacobi variants
+# the Jacobi workload: Jacobi variants
 # ----------------------------------------------------------------------------------------
 @pytest.mark.parametrize("n", [40, 256])
 def test_jacobi_record_and_eval(env, oracle, n):
@@ -116,7 +116,7 @@ def test_jacobi_record_and_eval(env, oracle, n):
 
 
 # ----------------------------------------------------------------------------------------
-# configs[4]: CSR SpMV launch configurations, write-set from the dirty-diff
+# the SpMV workload: CSR SpMV launch configurations, write-set from the dirty-diff
 # ----------------------------------------------------------------------------------------
 @pytest.mark.parametrize("rows", [1 << 15, 1 << 21])
 def test_spmv_record_and_sweep(env, oracle, rows):
@@ -178,7 +178,7 @@ def test_spmv_record_and_sweep(env, oracle, rows):
 
 
 # ----------------------------------------------------------------------------------------
-# configs[0]: ten pure restore -> validate replays
+# the small-replay workload: ten pure restore -> validate replays
 # ----------------------------------------------------------------------------------------
 def test_replay_small_ten_replays(env, oracle):
     r3, wl, ctx, torch = env
@@ -277,7 +277,7 @@ def test_eval_policies_and_failures(env, oracle):
 
 
 # ----------------------------------------------------------------------------------------
-# configs[3]: 16 x 2 GiB, full size
+# the large-snapshot workload: 16 x 2 GiB, full size
 # ----------------------------------------------------------------------------------------
 def test_large_snapshot_full_size(env, oracle):
     r3, wl, ctx, torch = env

@@ -51,7 +51,7 @@ def run_compare(r3, ctx, torch, rows, live, golden, arena_bytes):
 
 
 # ----------------------------------------------------------------------------------------
-# checksum and restore on many small regions (configs[2] shape, reduced and full)
+# checksum and restore on many small regions (the many-regions workload shape, reduced and full)
 # ----------------------------------------------------------------------------------------
 @pytest.mark.parametrize("n_regions,max_bytes,align", [(300, 1 << 18, 256), (300, 1 << 17, 1),
                                                        (64, 1 << 21, 16), (4096, 1 << 20, 256)])
@@ -120,7 +120,7 @@ def test_compare_mixed_tables(env, oracle, seed, align):
 
 
 def test_compare_replay_small_full_size(env, oracle):
-    """configs[0] at full size: 1049 planted mismatches among one-step perturbations."""
+    """the small-replay workload at full size: 1049 planted mismatches among one-step perturbations."""
     r3, ctx, torch = env
     c = ri.replay_small()
     exp_res, exp_sum = oracle.compare(oracle.make_table(c["check_rows"]), c["live"], c["epilogue"])
@@ -218,7 +218,7 @@ def test_compare_rounding_witnesses(env, oracle):
 
 
 def test_compare_large_snapshot_reduced(env, oracle):
-    """configs[3] shape at 8 x 8 MiB: planted counts and first indices, checksums of live."""
+    """the large-snapshot workload shape at 8 x 8 MiB: planted counts and first indices, checksums of live."""
     r3, ctx, torch = env
     c = ri.large_snapshot(n_regions=8, region_bytes=(8 << 20) + 4096 + 64, frac=1e-5)
     exp_res, exp_sum = oracle.compare(oracle.make_table(c["rows"]), c["snapshot"], c["golden"])
