@@ -31,9 +31,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # each scaled by what the same counter reads for a plain 1 GiB copy (FETCH 2.0, WRITE 1.0).
 # Valid only for the kernel source they were taken with: reported as null otherwise.
 COUNTERS = {
-    "kernels_sha256_16": "9d28edf09dea4bbc",
-    "jacobi": {"restore": 538987720, "validate": 269139871 + 339367},
-    "large_snapshot": {"restore": 68737314671, "validate": 68728810857 + 5339092 + 6176},
+    "kernels_sha256_16": "cb60077bf1311860",
+    "jacobi": {"restore": 541106721, "validate": 269487766},
+    "large_snapshot": {"restore": 68754617505, "validate": 68734145181},
 }
 
 
