@@ -110,6 +110,8 @@ __device__ __forceinline__ uint64_t dpp_sum(uint64_t v) { R3_DPP_REDUCE(uint64_t
 __device__ __forceinline__ uint32_t dpp_sum(uint32_t v) { R3_DPP_REDUCE(uint32_t, dpp32, 0u, op_add) }
 __device__ __forceinline__ uint32_t dpp_min(uint32_t v) { R3_DPP_REDUCE(uint32_t, dpp32, 0xFFFFFFFFu, op_min) }
 __device__ __forceinline__ uint64_t dpp_max(uint64_t v) { R3_DPP_REDUCE(uint64_t, dpp64, 0ull, op_max) }
+__device__ __forceinline__ uint64_t op_min(uint64_t a, uint64_t b) { return b < a ? b : a; }
+__device__ __forceinline__ uint64_t dpp_min(uint64_t v) { R3_DPP_REDUCE(uint64_t, dpp64, ~0ull, op_min) }
 #undef R3_DPP_REDUCE
 
 // One checksum term: word w under key k.
@@ -772,7 +774,7 @@ __global__ __launch_bounds__(BLOCK) void compare_finalize_kernel(TableDev t, r3_
                                                                  HostSlot* host_slot, uint64_t host_seq,
                                                                  const uint32_t* rep_counter) {
   constexpr int NW = BLOCK / 64;
-  constexpr int kAhead = 4;  // partials fetched per thread before any is folded
+  constexpr int kAhead = 8;  // partials fetched per thread before any is folded
   __shared__ uint64_t sh[5][NW];
   const uint32_t r = blockIdx.x;
   const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -801,26 +803,25 @@ __global__ __launch_bounds__(BLOCK) void compare_finalize_kernel(TableDev t, r3_
         f.cks += v[u][4];
       }
     }
-    f.count = wave_sum(f.count);
-    f.first = wave_min(f.first);
-    f.max_abs = wave_max(f.max_abs);
-    f.max_rel = wave_max(f.max_rel);
-    f.cks = wave_sum(f.cks);
+    f.count = dpp_sum(f.count);
+    f.first = dpp_min(f.first);
+    f.max_abs = dpp_max(f.max_abs);
+    f.max_rel = dpp_max(f.max_rel);
+    f.cks = dpp_sum(f.cks);
     if (NW > 1) {
       if (lane == 0) {
         sh[0][wave] = f.count; sh[1][wave] = f.first; sh[2][wave] = f.max_abs;
         sh[3][wave] = f.max_rel; sh[4][wave] = f.cks;
       }
       __syncthreads();
-      if (tid == 0) {
-        f = Folded{0, R3_NO_INDEX, 0, 0, 0};
-        for (int w = 0; w < NW; ++w) {
-          f.count += sh[0][w];
-          f.first = sh[1][w] < f.first ? sh[1][w] : f.first;
-          f.max_abs = sh[2][w] > f.max_abs ? sh[2][w] : f.max_abs;
-          f.max_rel = sh[3][w] > f.max_rel ? sh[3][w] : f.max_rel;
-          f.cks += sh[4][w];
-        }
+      if (wave == 0) {  // the first wavefront folds the per-wavefront values, again over DPP
+        const bool on = lane < (uint32_t)NW;
+        const uint64_t zero = 0, none = R3_NO_INDEX;
+        f.count = dpp_sum((uint64_t)(on ? sh[0][lane] : zero));
+        f.first = dpp_min((uint64_t)(on ? sh[1][lane] : none));
+        f.max_abs = dpp_max((uint64_t)(on ? sh[2][lane] : zero));
+        f.max_rel = dpp_max((uint64_t)(on ? sh[3][lane] : zero));
+        f.cks = dpp_sum((uint64_t)(on ? sh[4][lane] : zero));
       }
     }
     if (tid == 0) {

@@ -372,3 +372,22 @@ def test_region_larger_than_4_gib(env, oracle):
     assert lo < planted[0]
     assert int(exp_res[0]["mismatch_count"]) == 3
     assert int(exp_res[0]["first_mismatch"]) + lo == planted[0]
+
+
+def test_compare_many_regions_full_size(env, oracle):
+    """The many-regions workload at full size (4096 regions, ~0.5 GiB) through the fused compare:
+    the live state is the restored snapshot with a seeded handful of bytes changed."""
+    r3, ctx, torch = env
+    c = ri.many_regions()
+    rng = np.random.default_rng(4242)
+    rows = [(off, nb, dt, ri.TOL if i % 3 == 0 else ri.BITWISE, 1e-3, 1e-6)
+            for i, (off, nb, dt, _, _, _) in enumerate(c["rows"])]
+    live = c["snapshot"].copy()
+    idx = rng.choice(c["arena_bytes"], size=3000, replace=False)
+    live[idx] ^= rng.integers(1, 256, size=idx.size, dtype=np.uint8)
+    exp_res, exp_sum = oracle.compare(oracle.make_table(rows), live, c["snapshot"])
+    got_res, got_sum = run_compare(r3, ctx, torch, rows, dev(torch, live), dev(torch, c["snapshot"]),
+                                   c["arena_bytes"])
+    assert_results_equal(got_res, exp_res, "regions")
+    assert_results_equal(got_sum, exp_sum, "summary")
+    assert int(got_sum[0]["total_mismatch"]) > 1000
