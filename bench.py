@@ -31,9 +31,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # each scaled by what the same counter reads for a plain 1 GiB copy (FETCH 2.0, WRITE 1.0).
 # Valid only for the kernel source they were taken with: reported as null otherwise.
 COUNTERS = {
-    "kernels_sha256_16": "cb60077bf1311860",
-    "jacobi": {"restore": 541106721, "validate": 269487766},
-    "large_snapshot": {"restore": 68754617505, "validate": 68734145181},
+    "kernels_sha256_16": "c42d24e1274cac2b",
+    "jacobi": {"restore": 541102234, "validate": 269490078},
+    "large_snapshot": {"restore": 68754663393, "validate": 68734168164},
 }
 
 
