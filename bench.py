@@ -16,6 +16,7 @@ Workloads (shapes of the five benchmark configurations):
   spmv            CSR SpMV, 2^21 rows x 27 nnz, 64 launch configurations
 """
 import argparse
+import collections
 import json
 import os
 import sys
@@ -56,6 +57,9 @@ def parse():
     p.add_argument("--warmup", type=int, default=None)
     p.add_argument("--workload", default="jacobi",
                    choices=["jacobi", "replay_small", "many_regions", "large_snapshot", "spmv"])
+    p.add_argument("--inflight", type=int, default=2,
+                   help="evaluations kept in flight (r3_eval_submit / r3_eval_wait); 1 = the synchronous "
+                        "r3_eval_candidate")
     p.add_argument("--no-large", action="store_true", help="skip the extra large-snapshot leg")
     p.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     p.add_argument("--calibrate-copy", action="store_true",
@@ -137,6 +141,7 @@ class Replay:
             self.desc = "CSR SpMV 2^21 rows x 27 nnz fp64, 64 launch configurations, full-arena restore 688 MiB"
         self.arena_bytes = A
         self.d_regions = torch.zeros(40 * self.check_tbl.n, dtype=torch.uint8, device="cuda:0")
+        self.d_regions_ring = []  # one result array per evaluation in flight
         self.restore_bytes = 2 * self.restore_tbl.info()["total_bytes"]
         self.validate_bytes = 2 * self.check_tbl.info()["total_bytes"]
 
@@ -194,16 +199,48 @@ class Replay:
         return out
 
 
-def timed_run(rp, steps, warmup):
+    def submit(self, i, slot):
+        k = i % len(self.candidates)
+        while len(self.d_regions_ring) <= slot:
+            self.d_regions_ring.append(self.torch.zeros_like(self.d_regions))
+        t = self.r3.r3_eval_submit(self.ctx, self.restore_tbl, self.d_pro, self.check_tbl, self.d_epi,
+                                   self.d_live, self.launch, self.candidates[k], 0, 1, self.r3.EVERY,
+                                   self.d_regions_ring[slot])
+        return t, i, k
+
+    def finish(self, t, i, k):
+        rc, out = self.r3.r3_eval_wait(self.ctx, t)
+        want = self.expect_pass[k]
+        if rc != 0 or (want is not None and bool(out.passed) != want):
+            raise RuntimeError("evaluation %d of %s gave pass=%d (expected %s), status %d"
+                               % (i, self.name, out.passed, want, rc))
+        return out
+
+
+def run_steps(rp, n, inflight):
+    """n evaluations, each a whole restore -> candidate -> validate -> verdict on the host; with
+    inflight > 1 the next ones are enqueued before the verdict of the oldest is waited for."""
+    if inflight <= 1:
+        for i in range(n):
+            rp.step(i)
+        return
+    q = collections.deque()
+    for i in range(n):
+        q.append(rp.submit(i, i % inflight))
+        if len(q) == inflight:
+            rp.finish(*q.popleft())
+    while q:
+        rp.finish(*q.popleft())
+
+
+def timed_run(rp, steps, warmup, inflight=1):
     torch, ctx = rp.torch, rp.ctx
-    for i in range(warmup):
-        rp.step(i)
+    run_steps(rp, warmup, inflight)
     ctx.profile(4 if steps >= 16 else 1)  # stage events on every 4th evaluation of the timed region
     ctx.profile_read(reset=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(steps):
-        rp.step(i)
+    run_steps(rp, steps, inflight)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     prof = ctx.profile_read(reset=True)
@@ -432,7 +469,10 @@ def main():
         torch.cuda.empty_cache()
 
     rp = Replay(a.workload, r3, wl, ctx, torch)
-    dt, prof = timed_run(rp, steps, warmup)
+    if not 1 <= a.inflight <= 8:
+        print("--inflight must be 1 .. 8", file=sys.stderr)
+        sys.exit(2)
+    dt, prof = timed_run(rp, steps, warmup, a.inflight)
     stages = stage_report(rp, prof)
     line = {
         "metric": "candidate evals/sec per kernel; restore+compare GB/s as % of HBM peak",
@@ -440,10 +480,14 @@ def main():
         "ms_per_step": dt / steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f64" if a.workload in ("jacobi", "spmv") else "u8",
         "data": "synthetic",
-        "config": {"workload": "%s: %s" % (a.workload, rp.desc)},
+        "config": {"workload": "%s: %s" % (a.workload, rp.desc), "evaluations_in_flight": a.inflight},
         "roofline": roofline(rp, stages),
         "stages": stages,
     }
+    if a.inflight > 1:
+        dt1, _ = timed_run(rp, steps, warmup, 1)
+        line["synchronous"] = {"value": steps / dt1, "unit": "evals/s", "ms_per_step": dt1 / steps * 1e3,
+                               "note": "the same evaluations through r3_eval_candidate, one at a time"}
     cpu = None if a.no_cpu else cpu_baseline(rp)
     line["cpu_baseline"] = cpu
     line["record_path"] = record_path_leg(rp)

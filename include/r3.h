@@ -70,6 +70,7 @@ typedef enum { R3_POLICY_EVERY = 0, R3_POLICY_FIRST = 1, R3_POLICY_LAST = 2 } r3
 #define R3_NO_INDEX UINT64_MAX   /* first_mismatch / first_index when nothing mismatched */
 #define R3_NO_REGION UINT32_MAX  /* first_region when nothing mismatched                 */
 #define R3_MAX_REPLAYS 1024u     /* warmup + reps accepted by r3_eval_candidate          */
+#define R3_MAX_INFLIGHT 8u       /* evaluations submitted and not yet waited for         */
 
 /* One span of the arena (40 bytes, host memory, caller-owned).
  * offset and bytes are multiples of the element size; bytes may be 0.
@@ -296,6 +297,30 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
                       r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
                       uint32_t compare_policy, r3_region_result* d_regions,
                       r3_eval_result* host_out, void* stream);
+
+/* r3_eval_candidate in two halves, for a search that has several candidates ready at once
+ * (Section II-C: several controllers run the sample / evaluate / update cycle concurrently;
+ * Section V-D: replay workers persist across requests so that nothing is paid per candidate
+ * that can be paid once).  r3_eval_submit checks the arguments, enqueues all
+ * replays of one evaluation on the stream and returns a ticket without waiting; the host can
+ * enqueue the next evaluation while this one runs, which hides the launch latency between
+ * evaluations.  r3_eval_wait blocks until that evaluation's verdict is on the host and fills
+ * host_out exactly as r3_eval_candidate would have; the ticket is then free again.
+ * Evaluations submitted on one stream run in submission order, so they may share d_live, the
+ * snapshots and the tables; evaluations that share any of these must use the same stream.
+ * d_regions is overwritten by each evaluation that names it: give evaluations in flight
+ * different arrays if the per-region results of each are wanted.  At most R3_MAX_INFLIGHT
+ * tickets are outstanding (R3_ENOSPC beyond).  Tickets can be waited for in any order;
+ * r3_eval_candidate may be called while tickets are outstanding; r3_ctx_destroy waits for
+ * what is in flight.  A failing launch callback is reported by r3_eval_wait
+ * (R3_ECANDIDATE, pass = 0), not by r3_eval_submit.  Errors: as r3_eval_candidate;
+ * r3_eval_wait: R3_EINVAL for a ticket that is not outstanding. */
+int r3_eval_submit(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
+                   const r3_table* check_tbl, const void* d_epilogue, void* d_live,
+                   r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
+                   uint32_t compare_policy, r3_region_result* d_regions, uint32_t* ticket_out,
+                   void* stream);
+int r3_eval_wait(r3_ctx* ctx, uint32_t ticket, r3_eval_result* host_out);
 
 /* ---- write-set driven replay ------------------------------------------- */
 

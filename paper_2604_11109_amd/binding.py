@@ -72,6 +72,7 @@ DECLARED = [
     "r3_table_validate", "r3_table_workspace_bytes", "r3_table_workspace_bytes_exact",
     "r3_tune_tiles", "r3_tune_copy", "r3_table_create", "r3_table_destroy", "r3_table_info", "r3_restore",
     "r3_checksum", "r3_compare", "r3_dirty_diff", "r3_record", "r3_eval_candidate",
+    "r3_eval_submit", "r3_eval_wait",
     "r3_writeset_regions", "r3_eval_candidate_guarded", "r3_table_replicate",
     "r3_eval_candidate_instances", "r3_ctx_last_times", "r3_timing_stats",
     "r3_replay_workspace_bytes", "r3_replay_create", "r3_replay_run", "r3_replay_destroy",
@@ -123,6 +124,9 @@ def lib():
         L.r3_record.argtypes = [vp, vp, vp, vp, vp, vp, vp, u32, vp, vp, vp, vp, vp]
         L.r3_eval_candidate.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, u32, vp,
                                         ctypes.POINTER(EvalResult), vp]
+        L.r3_eval_submit.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, u32, vp,
+                                     ctypes.POINTER(u32), vp]
+        L.r3_eval_wait.argtypes = [vp, u32, ctypes.POINTER(EvalResult)]
         L.r3_writeset_regions.argtypes = [vp, u64, u32, ci, vp, u32, ctypes.POINTER(u32)]
         L.r3_eval_candidate_guarded.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, u32, vp,
                                                 ctypes.POINTER(EvalResult), ctypes.POINTER(Guard),
@@ -391,6 +395,33 @@ def r3_eval_candidate(ctx, restore_tbl, d_prologue, check_tbl, d_epilogue, d_liv
     if rc == ECANDIDATE and not raise_on_candidate:
         return rc, out
     ctx.check(rc, "r3_eval_candidate")
+    return rc, out
+
+
+def r3_eval_submit(ctx, restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, launch, user,
+                   warmup, reps, policy, d_regions, stream=None):
+    """Enqueue one evaluation without waiting; returns its ticket."""
+    _need(d_prologue, restore_tbl.arena_bytes, "prologue")
+    _need(d_epilogue, check_tbl.arena_bytes, "epilogue")
+    _need(d_live, max(restore_tbl.arena_bytes, check_tbl.arena_bytes), "live arena")
+    _need(d_regions, 40 * check_tbl.n, "region results")
+    fn, usr, keep = _launch_args(launch, user)
+    ticket = ctypes.c_uint32(0)
+    rc = lib().r3_eval_submit(ctx.handle, restore_tbl.handle, _ptr(d_prologue), check_tbl.handle,
+                              _ptr(d_epilogue), _ptr(d_live), fn, _ptr(usr), warmup, reps, policy,
+                              _ptr(d_regions), ctypes.byref(ticket), _stream(stream))
+    del keep
+    ctx.check(rc, "r3_eval_submit")
+    return ticket.value
+
+
+def r3_eval_wait(ctx, ticket, raise_on_candidate=False):
+    """Returns (status, EvalResult) of a submitted evaluation; status is OK or ECANDIDATE."""
+    out = EvalResult()
+    rc = lib().r3_eval_wait(ctx.handle, ticket, ctypes.byref(out))
+    if rc == ECANDIDATE and not raise_on_candidate:
+        return rc, out
+    ctx.check(rc, "r3_eval_wait")
     return rc, out
 
 

@@ -46,6 +46,39 @@ int check_common(r3_ctx* ctx, const r3_table* tbl) {
   return R3_OK;
 }
 
+// Pinned verdict slots of a lane, allocated the first time the lane is used.
+int lane_init(r3_ctx* ctx, r3::EvalLane& lane) {
+  if (lane.pinned != nullptr) return R3_OK;
+  hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&lane.pinned),
+                               R3_MAX_REPLAYS * sizeof(r3::HostSlot), hipHostMallocMapped);
+  if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void**>(&lane.pinned_dev), lane.pinned, 0);
+  if (e == hipSuccess)
+    e = hipHostMalloc(reinterpret_cast<void**>(&lane.guard_pinned), R3_MAX_REPLAYS * sizeof(r3::GuardSlot),
+                      hipHostMallocMapped);
+  if (e == hipSuccess)
+    e = hipHostGetDevicePointer(reinterpret_cast<void**>(&lane.guard_pinned_dev), lane.guard_pinned, 0);
+  if (e == hipSuccess) e = hipEventCreate(&lane.end_event);
+  if (e != hipSuccess) {
+    if (lane.guard_pinned) (void)hipHostFree(lane.guard_pinned);
+    if (lane.pinned) (void)hipHostFree(lane.pinned);
+    lane.pinned = nullptr;
+    lane.guard_pinned = nullptr;
+    return fail_hip(ctx, e, "pinned verdict slots");
+  }
+  return R3_OK;
+}
+
+void lane_release(r3::EvalLane& lane) {
+  for (hipEvent_t e : lane.events) (void)hipEventDestroy(e);
+  lane.events.clear();
+  if (lane.end_event) (void)hipEventDestroy(lane.end_event);
+  if (lane.pinned) (void)hipHostFree(lane.pinned);
+  if (lane.guard_pinned) (void)hipHostFree(lane.guard_pinned);
+  lane.pinned = nullptr;
+  lane.guard_pinned = nullptr;
+  lane.end_event = nullptr;
+}
+
 }  // namespace
 
 extern "C" {
@@ -75,19 +108,7 @@ int r3_ctx_create(r3_ctx** out, int device) {
   if (ctx == nullptr) return R3_ENOSPC;
   ctx->device = device;
   DeviceGuard guard(device);
-  if (!guard.ok ||
-      hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned), R3_MAX_REPLAYS * sizeof(r3::HostSlot),
-                    hipHostMallocMapped) != hipSuccess) {
-    delete ctx;
-    return R3_EHIP;
-  }
-  if (hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->pinned_dev), ctx->pinned, 0) != hipSuccess ||
-      hipHostMalloc(reinterpret_cast<void**>(&ctx->guard_pinned), R3_MAX_REPLAYS * sizeof(r3::GuardSlot),
-                    hipHostMallocMapped) != hipSuccess ||
-      hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->guard_pinned_dev), ctx->guard_pinned, 0) !=
-          hipSuccess) {
-    if (ctx->guard_pinned) (void)hipHostFree(ctx->guard_pinned);
-    (void)hipHostFree(ctx->pinned);
+  if (!guard.ok || lane_init(ctx, ctx->lanes[0]) != R3_OK) {
     delete ctx;
     return R3_EHIP;
   }
@@ -98,9 +119,10 @@ int r3_ctx_create(r3_ctx** out, int device) {
 int r3_ctx_destroy(r3_ctx* ctx) {
   if (ctx == nullptr) return R3_EINVAL;
   DeviceGuard guard(ctx->device);
-  for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
-  if (ctx->pinned) (void)hipHostFree(ctx->pinned);
-  if (ctx->guard_pinned) (void)hipHostFree(ctx->guard_pinned);
+  // Work that still posts into a lane's pinned memory must have run before the memory goes.
+  for (r3::EvalLane& lane : ctx->lanes)
+    if (lane.busy) (void)hipStreamSynchronize(lane.stream);
+  for (r3::EvalLane& lane : ctx->lanes) lane_release(lane);
   delete ctx;
   return R3_OK;
 }
@@ -292,12 +314,14 @@ int r3_record(r3_ctx* ctx, const r3_table* tbl, void* d_live, r3_launch_fn launc
   return e == hipSuccess ? R3_OK : fail_hip(ctx, e, "record wait");
 }
 
-static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
-                     const r3_table* check_tbl, const void* d_epilogue, void* d_live,
-                     r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
-                     uint32_t compare_policy, r3_region_result* d_regions, r3_eval_result* host_out,
-                     const r3_guard* guard, r3_guard_result* host_guard_out, uint32_t instances,
-                     uint64_t instance_stride, void* stream) {
+// First half of an evaluation: check the arguments and enqueue every replay on the stream.
+// Returns before any of it has run.  R3_OK means the lane is busy and eval_collect must follow,
+// also when the candidate's callback failed (that is part of the verdict).
+static int eval_enqueue(r3_ctx* ctx, r3::EvalLane& lane, const r3_table* restore_tbl, const void* d_prologue,
+                        const r3_table* check_tbl, const void* d_epilogue, void* d_live,
+                        r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
+                        uint32_t compare_policy, r3_region_result* d_regions, const r3_guard* guard,
+                        uint32_t instances, uint64_t instance_stride, bool mark_end, void* stream) {
   int rc = check_common(ctx, restore_tbl);
   if (rc == R3_OK) rc = check_common(ctx, check_tbl);
   if (rc != R3_OK) return rc;
@@ -308,12 +332,7 @@ static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pro
     if (guard->d_expected == nullptr || guard->d_scratch == nullptr)
       return fail(ctx, R3_EINVAL, "guard pointer is NULL");
   }
-  if (host_guard_out) {
-    std::memset(host_guard_out, 0, sizeof(*host_guard_out));
-    host_guard_out->first_region = R3_NO_REGION;
-  }
-  if (d_prologue == nullptr || d_epilogue == nullptr || d_live == nullptr || d_regions == nullptr ||
-      host_out == nullptr)
+  if (d_prologue == nullptr || d_epilogue == nullptr || d_live == nullptr || d_regions == nullptr)
     return fail(ctx, R3_EINVAL, "pointer is NULL");
   if (!aligned16(d_prologue) || !aligned16(d_epilogue) || !aligned16(d_live))
     return fail(ctx, R3_EALIGN, "arena base not 16-byte aligned");
@@ -321,42 +340,52 @@ static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pro
   const uint64_t total = (uint64_t)warmup + reps;
   if (reps == 0) return fail(ctx, R3_EINVAL, "reps must be at least 1");
   if (total > R3_MAX_REPLAYS) return fail(ctx, R3_ENOSPC, "warmup + reps exceeds R3_MAX_REPLAYS");
+  if (lane.busy) return fail(ctx, R3_EINVAL, "an evaluation is still in flight here");
 
   DeviceGuard device_guard(ctx->device);
+  rc = lane_init(ctx, lane);
+  if (rc != R3_OK) return rc;
   hipStream_t s = as_stream(stream);
   // Events of replay r: [4r] before the restore and [4r+3] after the validation (only when
   // profiling), [4r+1] / [4r+2] around the candidate.
   const bool prof = ctx->profile_period != 0 && (ctx->evals++ % ctx->profile_period) == 0;
-  while (ctx->events.size() < 4 * total) {
+  while (lane.events.size() < 4 * total) {
     hipEvent_t ev;
     hipError_t e = hipEventCreate(&ev);
     if (e != hipSuccess) return fail_hip(ctx, e, "event create");
-    ctx->events.push_back(ev);
+    lane.events.push_back(ev);
   }
 
-  std::memset(host_out, 0, sizeof(*host_out));
-  host_out->first_index = R3_NO_INDEX;
-  host_out->first_region = R3_NO_REGION;
+  lane.prof = prof;
+  lane.has_launch = launch != nullptr;
+  lane.has_guard = guard != nullptr;
+  lane.guard = guard ? *guard : r3_guard{};
+  lane.warmup = warmup;
+  lane.total = (uint32_t)total;
+  lane.done = 0;
+  lane.n_validated = 0;
+  lane.cand = 0;
+  lane.validated.assign(total, 0);
+  lane.guarded.assign(total, 0);
+  lane.last_flag = nullptr;
+  lane.last_want = 0;
+  lane.end_recorded = false;
+  lane.stream = s;
+  lane.d_prologue = d_prologue;
+  lane.d_live = d_live;
 
-  uint32_t n_validated = 0;
   int cand = 0;
   hipError_t e = hipSuccess;
-  uint32_t done = 0;
-  std::vector<uint8_t> validated(total, 0);
-  // The sequence number that the last work enqueued will post in pinned memory, if it does.
-  const uint64_t* last_flag = nullptr;
-  uint64_t last_want = 0;
-  std::vector<uint8_t> guarded(total, 0);
   for (uint32_t rep = 0; rep < total; ++rep) {
-    last_flag = nullptr;
+    lane.last_flag = nullptr;
     if (prof) {
-      e = hipEventRecord(ctx->events[4 * rep], s);
+      e = hipEventRecord(lane.events[4 * rep], s);
       if (e != hipSuccess) break;
     }
     e = r3::launch_restore(restore_tbl->dev, restore_tbl->class_count, d_prologue, d_live, s);
     if (e != hipSuccess) break;
     if (launch || prof) {
-      e = hipEventRecord(ctx->events[4 * rep + 1], s);
+      e = hipEventRecord(lane.events[4 * rep + 1], s);
       if (e != hipSuccess) break;
     }
     if (launch) {
@@ -368,7 +397,7 @@ static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pro
       if (cand != 0) break;
     }
     if (launch || prof) {
-      e = hipEventRecord(ctx->events[4 * rep + 2], s);
+      e = hipEventRecord(lane.events[4 * rep + 2], s);
       if (e != hipSuccess) break;
     }
     const bool validate = compare_policy == R3_POLICY_EVERY ||
@@ -376,14 +405,14 @@ static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pro
                           (compare_policy == R3_POLICY_LAST && rep == total - 1);
     if (validate) {
       e = r3::launch_compare(check_tbl->dev, d_live, d_epilogue, d_regions, nullptr,
-                             &ctx->pinned_dev[n_validated], ++ctx->seq, nullptr, s);
-      last_flag = &ctx->pinned[n_validated].seq;
-      last_want = ctx->seq;
+                             &lane.pinned_dev[lane.n_validated], ++ctx->seq, nullptr, s);
+      lane.last_flag = &lane.pinned[lane.n_validated].seq;
+      lane.last_want = ctx->seq;
       if (e != hipSuccess) break;
-      ++n_validated;
-      validated[rep] = 1;
+      ++lane.n_validated;
+      lane.validated[rep] = 1;
       if (prof) {
-        e = hipEventRecord(ctx->events[4 * rep + 3], s);
+        e = hipEventRecord(lane.events[4 * rep + 3], s);
         if (e != hipSuccess) break;
       }
     }
@@ -391,24 +420,55 @@ static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pro
       e = r3::launch_checksum(guard->guard_tbl->dev, d_live, guard->d_scratch, s);
       if (e == hipSuccess)
         e = r3::launch_guard_compare(guard->d_scratch, guard->d_expected, guard->guard_tbl->dev.n_regions,
-                                     &ctx->guard_pinned_dev[rep], ++ctx->seq, s);
+                                     &lane.guard_pinned_dev[rep], ++ctx->seq, s);
       if (e != hipSuccess) break;
-      guarded[rep] = 1;
-      last_flag = &ctx->guard_pinned[rep].seq;
-      last_want = ctx->seq;
+      lane.guarded[rep] = 1;
+      lane.last_flag = &lane.guard_pinned[rep].seq;
+      lane.last_want = ctx->seq;
     }
-    ++done;
+    ++lane.done;
   }
-  // Wait for the verdict.  When the last thing enqueued is a validation, its sequence number
-  // arriving in pinned memory says that everything before it on the stream has run; polling
-  // for it (bounded) avoids the wake-up latency of a stream wait.  Anything else, and any
-  // doubt, takes the stream wait.
+  lane.cand = cand;
+  lane.status = e;
+  if (e != hipSuccess || cand != 0) lane.last_flag = nullptr;
+  // A submission whose end posts no number is marked with an event, so that waiting for it
+  // does not have to wait for whatever was enqueued on the stream afterwards.
+  if (mark_end && lane.last_flag == nullptr && e == hipSuccess)
+    lane.end_recorded = hipEventRecord(lane.end_event, s) == hipSuccess;
+  lane.busy = true;
+  return R3_OK;
+}
+
+// Second half: wait for the verdict of the evaluation enqueued on this lane and report it.
+static int eval_collect(r3_ctx* ctx, r3::EvalLane& lane, r3_eval_result* host_out,
+                        r3_guard_result* host_guard_out) {
+  DeviceGuard device_guard(ctx->device);
+  hipStream_t s = lane.stream;
+  const uint32_t total = lane.total, done = lane.done;
+  hipError_t e = lane.status;
+  const int cand = lane.cand;
+  lane.busy = false;
+
+  std::memset(host_out, 0, sizeof(*host_out));
+  host_out->first_index = R3_NO_INDEX;
+  host_out->first_region = R3_NO_REGION;
+  if (host_guard_out) {
+    std::memset(host_guard_out, 0, sizeof(*host_guard_out));
+    host_guard_out->first_region = R3_NO_REGION;
+  }
+
+  // When the last thing enqueued is a validation, its sequence number arriving in pinned memory
+  // says that everything before it on the stream has run; polling for it (bounded) avoids the
+  // wake-up latency of a stream wait.  Anything else, and any doubt, takes the event or the
+  // stream wait.
   bool arrived = false;
-  if (e == hipSuccess && cand == 0 && last_flag != nullptr) {
+  if (lane.last_flag != nullptr) {
     for (uint32_t spin = 0; spin < (1u << 22) && !arrived; ++spin)
-      arrived = __atomic_load_n(last_flag, __ATOMIC_ACQUIRE) == last_want;
-    if (arrived && prof && validated[total - 1])
-      arrived = hipEventSynchronize(ctx->events[4 * (total - 1) + 3]) == hipSuccess;
+      arrived = __atomic_load_n(lane.last_flag, __ATOMIC_ACQUIRE) == lane.last_want;
+    if (arrived && lane.prof && lane.validated[total - 1])
+      arrived = hipEventSynchronize(lane.events[4 * (total - 1) + 3]) == hipSuccess;
+  } else if (lane.end_recorded) {
+    arrived = hipEventSynchronize(lane.end_event) == hipSuccess;
   }
   if (!arrived) {
     hipError_t we = hipStreamSynchronize(s);
@@ -417,22 +477,22 @@ static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pro
   if (e != hipSuccess) return fail_hip(ctx, e, "replay loop");
 
   host_out->candidate_status = cand;
-  for (uint32_t i = 0; i < n_validated; ++i)
-    host_out->total_mismatch = std::max(host_out->total_mismatch, ctx->pinned[i].summary.total_mismatch);
-  if (n_validated) {
-    const r3_summary& last = ctx->pinned[n_validated - 1].summary;
+  for (uint32_t i = 0; i < lane.n_validated; ++i)
+    host_out->total_mismatch = std::max(host_out->total_mismatch, lane.pinned[i].summary.total_mismatch);
+  if (lane.n_validated) {
+    const r3_summary& last = lane.pinned[lane.n_validated - 1].summary;
     host_out->first_index = last.first_index;
     host_out->first_region = last.first_region;
     host_out->max_abs_err = last.max_abs_err;
     host_out->max_rel_err = last.max_rel_err;
   }
   host_out->pass = (cand == 0 && host_out->total_mismatch == 0) ? 1u : 0u;
-  if (guard) {
+  if (lane.has_guard) {
     r3_guard_result g{};
     g.first_region = R3_NO_REGION;
     for (uint32_t rep = 0; rep < done; ++rep) {
-      if (!guarded[rep]) continue;
-      const r3::GuardSlot& gs = ctx->guard_pinned[rep];
+      if (!lane.guarded[rep]) continue;
+      const r3::GuardSlot& gs = lane.guard_pinned[rep];
       ++g.checks;
       if (gs.changed) {
         if (g.failed_checks == 0) g.first_region = (uint32_t)gs.first_region;
@@ -442,8 +502,9 @@ static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pro
     }
     if (g.failed_checks) {
       host_out->pass = 0;
-      if (guard->heal_tbl) {
-        hipError_t he = r3::launch_restore(guard->heal_tbl->dev, guard->heal_tbl->class_count, d_prologue, d_live, s);
+      if (lane.guard.heal_tbl) {
+        hipError_t he = r3::launch_restore(lane.guard.heal_tbl->dev, lane.guard.heal_tbl->class_count,
+                                           lane.d_prologue, lane.d_live, s);
         if (he == hipSuccess) he = hipStreamSynchronize(s);
         if (he != hipSuccess) return fail_hip(ctx, he, "heal restore");
         g.healed = 1;
@@ -454,11 +515,11 @@ static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pro
 
   // Candidate times of the replays after the warm-up that ran to the end.
   ctx->last_times.clear();
-  if (launch) {
+  if (lane.has_launch) {
     std::vector<float> ms;
-    for (uint32_t rep = warmup; rep < done; ++rep) {
+    for (uint32_t rep = lane.warmup; rep < done; ++rep) {
       float t = 0.f;
-      if (hipEventElapsedTime(&t, ctx->events[4 * rep + 1], ctx->events[4 * rep + 2]) == hipSuccess)
+      if (hipEventElapsedTime(&t, lane.events[4 * rep + 1], lane.events[4 * rep + 2]) == hipSuccess)
         ms.push_back(t);
     }
     ctx->last_times = ms;
@@ -470,20 +531,20 @@ static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pro
                                           : 0.5f * (ms[ms.size() / 2 - 1] + ms[ms.size() / 2]);
     }
   }
-  if (prof) {
+  if (lane.prof) {
     for (uint32_t rep = 0; rep < done; ++rep) {
       float t = 0.f;
-      if (hipEventElapsedTime(&t, ctx->events[4 * rep], ctx->events[4 * rep + 1]) == hipSuccess) {
+      if (hipEventElapsedTime(&t, lane.events[4 * rep], lane.events[4 * rep + 1]) == hipSuccess) {
         ctx->profile.restore_ms += t;
         ctx->profile.restore_launches += 1;
       }
-      if (launch &&
-          hipEventElapsedTime(&t, ctx->events[4 * rep + 1], ctx->events[4 * rep + 2]) == hipSuccess) {
+      if (lane.has_launch &&
+          hipEventElapsedTime(&t, lane.events[4 * rep + 1], lane.events[4 * rep + 2]) == hipSuccess) {
         ctx->profile.candidate_ms += t;
         ctx->profile.candidate_launches += 1;
       }
-      if (validated[rep] &&
-          hipEventElapsedTime(&t, ctx->events[4 * rep + 2], ctx->events[4 * rep + 3]) == hipSuccess) {
+      if (lane.validated[rep] &&
+          hipEventElapsedTime(&t, lane.events[4 * rep + 2], lane.events[4 * rep + 3]) == hipSuccess) {
         ctx->profile.validate_ms += t;
         ctx->profile.validate_launches += 1;
       }
@@ -491,6 +552,47 @@ static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pro
   }
   if (cand != 0) return fail(ctx, R3_ECANDIDATE, "the candidate failed to launch");
   return R3_OK;
+}
+
+static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
+                     const r3_table* check_tbl, const void* d_epilogue, void* d_live,
+                     r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
+                     uint32_t compare_policy, r3_region_result* d_regions, r3_eval_result* host_out,
+                     const r3_guard* guard, r3_guard_result* host_guard_out, uint32_t instances,
+                     uint64_t instance_stride, void* stream) {
+  if (ctx == nullptr) return R3_EINVAL;
+  if (host_out == nullptr) return fail(ctx, R3_EINVAL, "pointer is NULL");
+  int rc = eval_enqueue(ctx, ctx->lanes[0], restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, launch,
+                        user, warmup, reps, compare_policy, d_regions, guard, instances, instance_stride,
+                        false, stream);
+  if (rc != R3_OK) return rc;
+  return eval_collect(ctx, ctx->lanes[0], host_out, host_guard_out);
+}
+
+int r3_eval_submit(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
+                   const r3_table* check_tbl, const void* d_epilogue, void* d_live, r3_launch_fn launch,
+                   void* user, uint32_t warmup, uint32_t reps, uint32_t compare_policy,
+                   r3_region_result* d_regions, uint32_t* ticket_out, void* stream) {
+  if (ctx == nullptr) return R3_EINVAL;
+  if (ticket_out == nullptr) return fail(ctx, R3_EINVAL, "pointer is NULL");
+  *ticket_out = 0;
+  uint32_t lane = 0;
+  for (uint32_t i = 1; i <= R3_MAX_INFLIGHT && lane == 0; ++i)
+    if (!ctx->lanes[i].busy) lane = i;
+  if (lane == 0) return fail(ctx, R3_ENOSPC, "R3_MAX_INFLIGHT evaluations are in flight already");
+  int rc = eval_enqueue(ctx, ctx->lanes[lane], restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, launch,
+                        user, warmup, reps, compare_policy, d_regions, nullptr, 1, 0, true, stream);
+  if (rc == R3_OK) *ticket_out = lane;
+  return rc;
+}
+
+int r3_eval_wait(r3_ctx* ctx, uint32_t ticket, r3_eval_result* host_out) {
+  if (ctx == nullptr) return R3_EINVAL;
+  ctx->err.clear();
+  if (host_out == nullptr) return fail(ctx, R3_EINVAL, "pointer is NULL");
+  if (ticket == 0 || ticket > R3_MAX_INFLIGHT || !ctx->lanes[ticket].busy)
+    return fail(ctx, R3_EINVAL, "no evaluation in flight under this ticket");
+  return eval_collect(ctx, ctx->lanes[ticket], host_out, nullptr);
 }
 
 int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,

@@ -145,18 +145,45 @@ hipError_t launch_dirty_diff(const void* pre, const void* post, uint64_t bytes, 
 
 }  // namespace r3
 
+namespace r3 {
+
+// What one evaluation in flight owns: its verdict slots in pinned host memory, its events, and
+// what the host has to remember between enqueueing the work and reading the verdict.
+struct EvalLane {
+  HostSlot* pinned = nullptr;      // R3_MAX_REPLAYS slots, pinned host memory
+  HostSlot* pinned_dev = nullptr;  // the same memory as the device addresses it
+  GuardSlot* guard_pinned = nullptr;  // R3_MAX_REPLAYS slots, pinned host memory
+  GuardSlot* guard_pinned_dev = nullptr;
+  std::vector<hipEvent_t> events;  // 4 per replay, grown on demand
+  hipEvent_t end_event = nullptr;  // marks the end of a submission whose last work posts no number
+
+  bool busy = false;  // enqueued, verdict not yet collected
+  bool prof = false;
+  bool has_launch = false;
+  bool has_guard = false;
+  bool end_recorded = false;
+  uint32_t warmup = 0, total = 0, done = 0, n_validated = 0;
+  int cand = 0;                        // status of the candidate callback
+  hipError_t status = hipSuccess;      // status of the enqueueing
+  std::vector<uint8_t> validated, guarded;  // per replay: validation / guard check enqueued
+  const uint64_t* last_flag = nullptr;      // where the last work enqueued posts its number, if it does
+  uint64_t last_want = 0;
+  hipStream_t stream = nullptr;
+  r3_guard guard{};
+  const void* d_prologue = nullptr;
+  void* d_live = nullptr;
+};
+
+}  // namespace r3
+
 struct r3_ctx {
   int device = 0;
   std::string err;
-  r3::HostSlot* pinned = nullptr;      // R3_MAX_REPLAYS slots, pinned host memory
-  r3::HostSlot* pinned_dev = nullptr;  // the same memory as the device addresses it
-  r3::GuardSlot* guard_pinned = nullptr;      // R3_MAX_REPLAYS slots, pinned host memory
-  r3::GuardSlot* guard_pinned_dev = nullptr;
+  r3::EvalLane lanes[1 + R3_MAX_INFLIGHT];  // [0]: the synchronous calls; the rest: tickets
   uint64_t seq = 0;                    // sequence number of the last validation enqueued
   std::vector<float> last_times;       // candidate ms of the timed replays of the last evaluation
   uint32_t profile_period = 0;         // 0 = off, n = stage events on every n-th evaluation
   uint64_t evals = 0;
-  std::vector<hipEvent_t> events;  // 4 per replay, grown on demand
   r3_profile profile{};
 };
 

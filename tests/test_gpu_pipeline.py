@@ -1,0 +1,178 @@
+"""GPU parity of r3_eval_submit / r3_eval_wait: several evaluations in flight on one stream must
+give, ticket by ticket, what the oracle's evaluation loop gives for the same candidates."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import r3_inputs as ri
+from test_gpu_eval import assert_results_equal, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2604_11109_amd import binding as r3
+    from paper_2604_11109_amd import workloads as wl
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    r3.lib()
+    wl.lib()
+    ctx = r3.Context(0)
+    yield r3, wl, ctx, torch
+    ctx.close()
+
+
+def test_submit_wait_matches_oracle(env, oracle):
+    r3, wl, ctx, torch = env
+    rng = np.random.default_rng(77)
+    n = 1 << 18
+    half = n // 2
+    pro = rng.integers(0, 256, size=n, dtype=np.uint8)
+    epi = pro.copy()
+    epi[half:] = pro[:half] + 1
+    rrows = [(0, n, ri.U8, ri.BITWISE, 0, 0)]
+    crows = [(0, half, ri.U8, ri.BITWISE, 0, 0), (half, half, ri.U8, ri.BITWISE, 0, 0)]
+    rt, ct = r3.Table(ctx, rrows, n), r3.Table(ctx, crows, n)
+    d_pro, d_epi = dev(torch, pro), dev(torch, epi)
+    d_live = torch.zeros(n, dtype=torch.uint8, device="cuda:0")
+    max_inflight = 8
+    d_regions = [torch.zeros(80, dtype=torch.uint8, device="cuda:0") for _ in range(max_inflight)]
+
+    # candidate c flips the bytes wrong[c] of the output in the replay bad_at[c]
+    wrong = [sorted(int(x) for x in rng.choice(n, size=1 + c % 3, replace=False)) for c in range(max_inflight)]
+    bad_at = [None, 0, 1, 2, None, 3, 0, 1]
+    cases = [(0, 4, r3.EVERY), (2, 2, r3.EVERY), (0, 4, r3.FIRST), (1, 3, r3.LAST),
+             (0, 1, r3.EVERY), (0, 4, r3.EVERY), (0, 2, r3.LAST), (3, 1, r3.FIRST)]
+
+    def gpu_candidate(c):
+        state = {"k": 0}
+
+        def run(live_ptr, stream):
+            d_live[half:] = d_live[:half] + 1
+            if state["k"] == bad_at[c]:
+                for w in wrong[c]:
+                    d_live[w] ^= 1
+            state["k"] += 1
+            return 0
+        return run
+
+    def cpu_candidate(c):
+        state = {"k": 0}
+
+        def run(live):
+            live[half:] = live[:half] + 1
+            if state["k"] == bad_at[c]:
+                for w in wrong[c]:
+                    live[w] ^= 1
+            state["k"] += 1
+            return 0
+        return run
+
+    expected = []
+    live = np.zeros(n, np.uint8)
+    for c, (warmup, reps, policy) in enumerate(cases):
+        expected.append(oracle.eval_candidate(oracle.make_table(rrows), pro, oracle.make_table(crows), epi,
+                                              live, cpu_candidate(c), warmup, reps, policy))
+
+    for order in (list(range(max_inflight)), list(reversed(range(max_inflight))), [3, 0, 7, 1, 6, 2, 5, 4]):
+        tickets = []
+        for c, (warmup, reps, policy) in enumerate(cases):
+            tickets.append(r3.r3_eval_submit(ctx, rt, d_pro, ct, d_epi, d_live, gpu_candidate(c), None,
+                                             warmup, reps, policy, d_regions[c]))
+        assert sorted(tickets) == list(range(1, max_inflight + 1))
+        # no ticket left: the next submission is refused and changes nothing
+        with pytest.raises(r3.R3Error) as e:
+            r3.r3_eval_submit(ctx, rt, d_pro, ct, d_epi, d_live, None, None, 0, 1, r3.EVERY, d_regions[0])
+        assert e.value.status == r3.ENOSPC
+        for c in order:
+            rc, out = r3.r3_eval_wait(ctx, tickets[c])
+            exp = expected[c]
+            what = "candidate %d order %s" % (c, order)
+            assert rc == r3.OK, what
+            assert_results_equal(r3.results_to_numpy(d_regions[c], 2), exp["regions"], what)
+            assert (out.total_mismatch, out.passed) == (exp["total_mismatch"], exp["pass"]), what
+            assert (out.first_region, out.first_index) == (exp["first_region"], exp["first_index"]), what
+            assert out.ms_min > 0 and out.ms_min <= out.ms_median <= out.ms_max, what
+            # a ticket is spent once it has been waited for
+            with pytest.raises(r3.R3Error) as e:
+                r3.r3_eval_wait(ctx, tickets[c])
+            assert e.value.status == r3.EINVAL
+        # live memory holds what the last candidate submitted left
+        assert (host(d_live) == live).all()
+
+
+def test_submit_interleaved_with_synchronous_calls(env, oracle):
+    """A failing candidate is reported by the wait; the synchronous call works while tickets are out;
+    a pipeline of depth two over the Jacobi variants gives each variant's own verdict."""
+    r3, wl, ctx, torch = env
+    c = ri.jacobi(40)
+    A = c["arena_bytes"]
+    tbl = r3.Table(ctx, c["restore_rows"], A)
+    chk = r3.Table(ctx, c["check_rows"], A)
+    d_live = dev(torch, c["prologue"])
+    d_pro = torch.empty(A, dtype=torch.uint8, device="cuda:0")
+    d_epi = torch.empty(A, dtype=torch.uint8, device="cuda:0")
+    r3.r3_record(ctx, tbl, d_live, wl.jacobi_launch(), wl.jacobi_args(c, 64, 1, 0), d_pro, d_epi, 4096,
+                 None, None, None, None)
+    epi = host(d_epi)
+    nreg = len(c["check_rows"])
+    bufs = [torch.zeros(40 * nreg, dtype=torch.uint8, device="cuda:0") for _ in range(3)]
+
+    # what each variant gives when evaluated alone
+    alone = []
+    for block, unroll, bug in ri.JACOBI_VARIANTS:
+        rc, out = r3.r3_eval_candidate(ctx, tbl, d_pro, chk, d_epi, d_live, wl.jacobi_launch(),
+                                       wl.jacobi_args(c, block, unroll, bug), 0, 2, r3.EVERY, bufs[2])
+        exp_res, exp_sum = oracle.compare(oracle.make_table(c["check_rows"]), host(d_live), epi)
+        assert_results_equal(r3.results_to_numpy(bufs[2], nreg), exp_res, "alone")
+        assert out.total_mismatch == int(exp_sum[0]["total_mismatch"])
+        alone.append((exp_res, out))
+    assert [o.passed for _, o in alone].count(0) == 1
+
+    # depth two: submit variant i+1 before waiting for variant i
+    pending = None
+    got = []
+    for i, (block, unroll, bug) in enumerate(ri.JACOBI_VARIANTS):
+        t = r3.r3_eval_submit(ctx, tbl, d_pro, chk, d_epi, d_live, wl.jacobi_launch(),
+                              wl.jacobi_args(c, block, unroll, bug), 0, 2, r3.EVERY, bufs[i % 2])
+        if pending is not None:
+            rc, out = r3.r3_eval_wait(ctx, pending[0])
+            got.append((r3.results_to_numpy(bufs[pending[1] % 2], nreg).copy(), out))
+        pending = (t, i)
+    rc, out = r3.r3_eval_wait(ctx, pending[0])
+    got.append((r3.results_to_numpy(bufs[pending[1] % 2], nreg).copy(), out))
+    for i, ((exp_res, exp_out), (res, out)) in enumerate(zip(alone, got)):
+        what = "variant %d" % i
+        assert_results_equal(res, exp_res, what)
+        for f in ("total_mismatch", "first_region", "first_index", "passed", "max_abs_err", "max_rel_err"):
+            assert getattr(out, f) == getattr(exp_out, f), (what, f)
+
+    # a candidate that cannot be launched: the submission is accepted, the wait reports it
+    code = ctypes.c_int(9)
+    t_bad = r3.r3_eval_submit(ctx, tbl, d_pro, chk, d_epi, d_live, wl.failing_launch(), ctypes.addressof(code),
+                              0, 3, r3.EVERY, bufs[0])
+    t_good = r3.r3_eval_submit(ctx, tbl, d_pro, chk, d_epi, d_live, wl.jacobi_launch(),
+                               wl.jacobi_args(c, 64, 1, 0), 0, 1, r3.EVERY, bufs[1])
+    # the synchronous call while both are outstanding
+    rc, out = r3.r3_eval_candidate(ctx, tbl, d_pro, tbl, d_pro, d_live, None, None, 0, 1, r3.EVERY, bufs[2])
+    assert rc == r3.OK and out.passed == 1
+    rc, out = r3.r3_eval_wait(ctx, t_good)
+    assert rc == r3.OK and out.passed == 1 and out.candidate_status == 0
+    rc, out = r3.r3_eval_wait(ctx, t_bad)
+    assert rc == r3.ECANDIDATE and out.passed == 0 and out.candidate_status == 9
+    # argument errors are raised by the submission itself and take no ticket
+    with pytest.raises(r3.R3Error) as e:
+        r3.r3_eval_submit(ctx, tbl, d_pro, chk, d_epi, d_live, None, None, 0, 0, r3.EVERY, bufs[0])
+    assert e.value.status == r3.EINVAL
+    for bad_ticket in (0, 9, 3):
+        with pytest.raises(r3.R3Error) as e:
+            r3.r3_eval_wait(ctx, bad_ticket)
+        assert e.value.status == r3.EINVAL
+    tickets = [r3.r3_eval_submit(ctx, tbl, d_pro, tbl, d_pro, d_live, None, None, 0, 1, r3.EVERY, bufs[0])
+               for _ in range(8)]
+    assert sorted(tickets) == list(range(1, 9))
+    for t in tickets:
+        rc, out = r3.r3_eval_wait(ctx, t)
+        assert rc == r3.OK and out.passed == 1
