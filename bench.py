@@ -33,8 +33,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # Valid only for the kernel source they were taken with: reported as null otherwise.
 COUNTERS = {
     "kernels_sha256_16": "c42d24e1274cac2b",
-    "jacobi": {"restore": 541102234, "validate": 269490078},
-    "large_snapshot": {"restore": 68754663393, "validate": 68734168164},
+    "jacobi": {"restore": 541102336, "validate": 269490241},
+    "large_snapshot": {"restore": 68754996514, "validate": 68734158746},
 }
 
 
