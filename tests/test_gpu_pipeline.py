@@ -103,11 +103,13 @@ def test_submit_wait_matches_oracle(env, oracle):
         assert (host(d_live) == live).all()
 
 
-def test_submit_interleaved_with_synchronous_calls(env, oracle):
+@pytest.mark.parametrize("n", [40, 256])
+def test_submit_interleaved_with_synchronous_calls(env, oracle, n):
     """A failing candidate is reported by the wait; the synchronous call works while tickets are out;
     a pipeline of depth two over the Jacobi variants gives each variant's own verdict."""
     r3, wl, ctx, torch = env
-    c = ri.jacobi(40)
+    c = ri.jacobi(n)
+    print("case jacobi pipeline", n, flush=True)
     A = c["arena_bytes"]
     tbl = r3.Table(ctx, c["restore_rows"], A)
     chk = r3.Table(ctx, c["check_rows"], A)
