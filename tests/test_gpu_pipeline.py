@@ -178,3 +178,88 @@ def test_submit_interleaved_with_synchronous_calls(env, oracle, n):
     for t in tickets:
         rc, out = r3.r3_eval_wait(ctx, t)
         assert rc == r3.OK and out.passed == 1
+
+
+def test_several_units_resident(env, oracle):
+    """Three replay units (Jacobi, CSR SpMV, the small pure replay) stay resident side by side, each
+    with its own tables, snapshots and live arena; evaluations of all three are in flight together
+    on one stream and each verdict is the one that unit gives when evaluated alone."""
+    r3, wl, ctx, torch = env
+
+    def record(case, restore_rows, launch, args):
+        A = case["arena_bytes"]
+        tbl = r3.Table(ctx, restore_rows, A)
+        d_live = dev(torch, case["prologue"])
+        d_pro = torch.empty(A, dtype=torch.uint8, device="cuda:0")
+        d_epi = torch.empty(A, dtype=torch.uint8, device="cuda:0")
+        r3.r3_record(ctx, tbl, d_live, launch, args, d_pro, d_epi, 4096, None, None, None, None)
+        return tbl, d_live, d_pro, d_epi
+
+    units = []
+    cj = ri.jacobi(40)
+    tbl, d_live, d_pro, d_epi = record(cj, cj["restore_rows"], wl.jacobi_launch(), wl.jacobi_args(cj, 64, 1, 0))
+    units.append(dict(name="jacobi", restore=tbl, check=r3.Table(ctx, cj["check_rows"], cj["arena_bytes"]),
+                      rows=cj["check_rows"], live=d_live, pro=d_pro, epi=d_epi, launch=wl.jacobi_launch(),
+                      cands=[wl.jacobi_args(cj, b, u, g) for b, u, g in ri.JACOBI_VARIANTS]))
+    cs = ri.spmv(1 << 15)
+    tbl, d_live, d_pro, d_epi = record(cs, cs["table_rows"], wl.spmv_launch(), wl.spmv_args(cs, 64, 256))
+    units.append(dict(name="spmv", restore=tbl, check=r3.Table(ctx, cs["y_rows"], cs["arena_bytes"]),
+                      rows=cs["y_rows"], live=d_live, pro=d_pro, epi=d_epi, launch=wl.spmv_launch(),
+                      cands=[wl.spmv_args(cs, rpw, blk) for rpw, blk in ri.SPMV_VARIANTS[::9]]))
+    cr = ri.replay_small()
+    A = cr["arena_bytes"]
+    units.append(dict(name="small", restore=r3.Table(ctx, cr["restore_rows"], A),
+                      check=r3.Table(ctx, cr["check_rows"], A), rows=cr["check_rows"],
+                      live=dev(torch, cr["live"]), pro=dev(torch, cr["prologue"]), epi=dev(torch, cr["epilogue"]),
+                      launch=None, cands=[None, None]))
+
+    # each candidate of each unit alone, checked against the oracle on the bytes it left
+    for u in units:
+        u["alone"] = []
+        # one result array per evaluation that can be in flight
+        u["bufs"] = [torch.zeros(40 * len(u["rows"]), dtype=torch.uint8, device="cuda:0") for _ in range(6)]
+        epi = host(u["epi"])
+        for cand in u["cands"]:
+            rc, out = r3.r3_eval_candidate(ctx, u["restore"], u["pro"], u["check"], u["epi"], u["live"],
+                                           u["launch"], cand, 0, 1, r3.EVERY, u["bufs"][0])
+            assert rc == r3.OK
+            exp_res, exp_sum = oracle.compare(oracle.make_table(u["rows"]), host(u["live"]), epi)
+            assert_results_equal(r3.results_to_numpy(u["bufs"][0], len(u["rows"])), exp_res, u["name"])
+            assert out.total_mismatch == int(exp_sum[0]["total_mismatch"])
+            u["alone"].append((exp_res, out))
+    assert units[2]["alone"][0][1].total_mismatch == 1049
+
+    # round robin over the units, up to six evaluations in flight
+    work = []
+    most = max(len(u["cands"]) for u in units)
+    for k in range(most):
+        for ui, u in enumerate(units):
+            if k < len(u["cands"]):
+                work.append((ui, k))
+    inflight = []
+    done = 0
+
+    def collect():
+        ticket, ui, k, buf = inflight.pop(0)
+        u = units[ui]
+        rc, out = r3.r3_eval_wait(ctx, ticket)
+        exp_res, exp_out = u["alone"][k]
+        what = "%s candidate %d" % (u["name"], k)
+        assert rc == r3.OK, what
+        assert_results_equal(r3.results_to_numpy(buf, len(u["rows"])), exp_res, what)
+        for f in ("total_mismatch", "first_region", "first_index", "passed", "max_abs_err", "max_rel_err"):
+            assert getattr(out, f) == getattr(exp_out, f), (what, f)
+
+    for n_sub, (ui, k) in enumerate(work):
+        u = units[ui]
+        buf = u["bufs"][n_sub % 6]
+        t = r3.r3_eval_submit(ctx, u["restore"], u["pro"], u["check"], u["epi"], u["live"], u["launch"],
+                              u["cands"][k], 0, 1, r3.EVERY, buf)
+        inflight.append((t, ui, k, buf))
+        if len(inflight) == 6:
+            collect()
+            done += 1
+    while inflight:
+        collect()
+        done += 1
+    assert done == len(work)
