@@ -187,6 +187,32 @@ class Replay:
                                % (i, self.name, out.passed, want, rc))
         return out
 
+    def submit_writeset(self, i, slot, guard_every=8):
+        k = i % len(self.candidates)
+        while len(self.d_regions_ring) <= slot:
+            self.d_regions_ring.append(self.torch.zeros_like(self.d_regions))
+        guarded = i % guard_every == guard_every - 1
+        if guarded:
+            t = self.r3.r3_eval_submit_guarded(
+                self.ctx, self.ws_tbl, self.d_pro, self.check_tbl, self.d_epi, self.d_live, self.launch,
+                self.candidates[k], 0, 1, self.r3.EVERY, self.d_regions_ring[slot], self.guard_tbl,
+                self.d_expected, self.d_scratch, every=0, heal_tbl=self.heal_tbl)
+        else:
+            t = self.r3.r3_eval_submit(self.ctx, self.ws_tbl, self.d_pro, self.check_tbl, self.d_epi,
+                                       self.d_live, self.launch, self.candidates[k], 0, 1, self.r3.EVERY,
+                                       self.d_regions_ring[slot])
+        return t, i, k
+
+    def finish_writeset(self, t, i, k):
+        rc, out, g = self.r3.r3_eval_wait(self.ctx, t, with_guard=True)
+        if g.failed_checks:
+            raise RuntimeError("guard failed for candidate %d" % k)
+        want = self.expect_pass[k]
+        if rc != 0 or (want is not None and bool(out.passed) != want):
+            raise RuntimeError("write-set evaluation %d of %s gave pass=%d (expected %s), status %d"
+                               % (i, self.name, out.passed, want, rc))
+        return out
+
     def step(self, i):
         k = i % len(self.candidates)
         rc, out = self.r3.r3_eval_candidate(self.ctx, self.restore_tbl, self.d_pro, self.check_tbl,
@@ -248,20 +274,31 @@ def timed_run(rp, steps, warmup, inflight=1):
     return t1 - t0, prof
 
 
-def writeset_leg(rp, steps, warmup):
+def writeset_leg(rp, steps, warmup, inflight=1):
     """The same workload with write-set driven restore and a periodic whole-state guard."""
     info = rp.enable_writeset()
     torch = rp.torch
-    for i in range(warmup):
-        rp.step_writeset(i)
+
+    def run(n):
+        if inflight <= 1:
+            for i in range(n):
+                rp.step_writeset(i)
+            return
+        q = collections.deque()
+        for i in range(n):
+            q.append(rp.submit_writeset(i, i % inflight))
+            if len(q) == inflight:
+                rp.finish_writeset(*q.popleft())
+        while q:
+            rp.finish_writeset(*q.popleft())
+    run(warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(steps):
-        rp.step_writeset(i)
+    run(steps)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     info.update({"value": steps / dt, "unit": "evals/s", "ms_per_step": dt / steps * 1e3, "steps": steps,
-                 "guard_every": 8,
+                 "guard_every": 8, "evaluations_in_flight": inflight,
                  "note": "restore covers only the pages the recorded kernel wrote; every 8th evaluation also "
                          "checksums the rest of the arena against the recorded checksums"})
     return info
@@ -492,7 +529,7 @@ def main():
     line["cpu_baseline"] = cpu
     line["record_path"] = record_path_leg(rp)
     if a.workload in ("jacobi", "spmv"):
-        line["write_set_replay"] = writeset_leg(rp, steps, warmup)
+        line["write_set_replay"] = writeset_leg(rp, steps, warmup, a.inflight)
     del rp
     torch.cuda.empty_cache()
     if a.workload != "large_snapshot" and not a.no_large:

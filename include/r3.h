@@ -314,13 +314,16 @@ int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pr
  * r3_eval_candidate may be called while tickets are outstanding; r3_ctx_destroy waits for
  * what is in flight.  A failing launch callback is reported by r3_eval_wait
  * (R3_ECANDIDATE, pass = 0), not by r3_eval_submit.  Errors: as r3_eval_candidate;
- * r3_eval_wait: R3_EINVAL for a ticket that is not outstanding. */
+ * r3_eval_wait: R3_EINVAL for a ticket that is not outstanding.
+ * host_guard_out (host, may be NULL) is filled for evaluations submitted with
+ * r3_eval_submit_guarded (declared with the write-set calls below) and zeroed for others. */
 int r3_eval_submit(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
                    const r3_table* check_tbl, const void* d_epilogue, void* d_live,
                    r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
                    uint32_t compare_policy, r3_region_result* d_regions, uint32_t* ticket_out,
                    void* stream);
-int r3_eval_wait(r3_ctx* ctx, uint32_t ticket, r3_eval_result* host_out);
+int r3_eval_wait(r3_ctx* ctx, uint32_t ticket, r3_eval_result* host_out,
+                 r3_guard_result* host_guard_out);
 
 /* ---- write-set driven replay ------------------------------------------- */
 
@@ -344,6 +347,18 @@ int r3_eval_candidate_guarded(r3_ctx* ctx, const r3_table* restore_tbl, const vo
                               uint32_t compare_policy, r3_region_result* d_regions,
                               r3_eval_result* host_out, const r3_guard* guard,
                               r3_guard_result* host_guard_out, void* stream);
+
+/* r3_eval_candidate_guarded in two halves (see r3_eval_submit; the verdict and the guard result
+ * come from r3_eval_wait).  The guard structure is copied; what it points to must stay valid
+ * until the wait.  d_scratch may be shared by evaluations on one stream.  The heal table, if
+ * any, is restored by the r3_eval_wait that finds a failed check: evaluations that were in
+ * flight behind the failing one ran on the damaged state, fail their own final check and are
+ * to be submitted again. */
+int r3_eval_submit_guarded(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
+                           const r3_table* check_tbl, const void* d_epilogue, void* d_live,
+                           r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
+                           uint32_t compare_policy, r3_region_result* d_regions,
+                           const r3_guard* guard, uint32_t* ticket_out, void* stream);
 
 /* ---- several recorded instances of one kernel --------------------------- */
 

@@ -72,7 +72,7 @@ DECLARED = [
     "r3_table_validate", "r3_table_workspace_bytes", "r3_table_workspace_bytes_exact",
     "r3_tune_tiles", "r3_tune_copy", "r3_table_create", "r3_table_destroy", "r3_table_info", "r3_restore",
     "r3_checksum", "r3_compare", "r3_dirty_diff", "r3_record", "r3_eval_candidate",
-    "r3_eval_submit", "r3_eval_wait",
+    "r3_eval_submit", "r3_eval_wait", "r3_eval_submit_guarded",
     "r3_writeset_regions", "r3_eval_candidate_guarded", "r3_table_replicate",
     "r3_eval_candidate_instances", "r3_ctx_last_times", "r3_timing_stats",
     "r3_replay_workspace_bytes", "r3_replay_create", "r3_replay_run", "r3_replay_destroy",
@@ -126,7 +126,9 @@ def lib():
                                         ctypes.POINTER(EvalResult), vp]
         L.r3_eval_submit.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, u32, vp,
                                      ctypes.POINTER(u32), vp]
-        L.r3_eval_wait.argtypes = [vp, u32, ctypes.POINTER(EvalResult)]
+        L.r3_eval_wait.argtypes = [vp, u32, ctypes.POINTER(EvalResult), ctypes.POINTER(GuardResult)]
+        L.r3_eval_submit_guarded.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, u32, vp,
+                                             ctypes.POINTER(Guard), ctypes.POINTER(u32), vp]
         L.r3_writeset_regions.argtypes = [vp, u64, u32, ci, vp, u32, ctypes.POINTER(u32)]
         L.r3_eval_candidate_guarded.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, u32, vp,
                                                 ctypes.POINTER(EvalResult), ctypes.POINTER(Guard),
@@ -415,14 +417,36 @@ def r3_eval_submit(ctx, restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, 
     return ticket.value
 
 
-def r3_eval_wait(ctx, ticket, raise_on_candidate=False):
-    """Returns (status, EvalResult) of a submitted evaluation; status is OK or ECANDIDATE."""
-    out = EvalResult()
-    rc = lib().r3_eval_wait(ctx.handle, ticket, ctypes.byref(out))
-    if rc == ECANDIDATE and not raise_on_candidate:
-        return rc, out
-    ctx.check(rc, "r3_eval_wait")
-    return rc, out
+def r3_eval_submit_guarded(ctx, restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, launch, user,
+                           warmup, reps, policy, d_regions, guard_tbl, d_expected, d_scratch,
+                           every=0, heal_tbl=None, stream=None):
+    """Enqueue one guarded evaluation without waiting; returns its ticket."""
+    _need(d_prologue, restore_tbl.arena_bytes, "prologue")
+    _need(d_epilogue, check_tbl.arena_bytes, "epilogue")
+    _need(d_live, max(restore_tbl.arena_bytes, check_tbl.arena_bytes, guard_tbl.arena_bytes), "live arena")
+    _need(d_regions, 40 * check_tbl.n, "region results")
+    _need(d_expected, 8 * guard_tbl.n, "guard checksums")
+    _need(d_scratch, 8 * guard_tbl.n, "guard scratch")
+    fn, usr, keep = _launch_args(launch, user)
+    g = Guard(guard_tbl.handle.value, _ptr(d_expected), _ptr(d_scratch),
+              heal_tbl.handle.value if heal_tbl is not None else None, every, 0)
+    ticket = ctypes.c_uint32(0)
+    rc = lib().r3_eval_submit_guarded(ctx.handle, restore_tbl.handle, _ptr(d_prologue), check_tbl.handle,
+                                      _ptr(d_epilogue), _ptr(d_live), fn, _ptr(usr), warmup, reps, policy,
+                                      _ptr(d_regions), ctypes.byref(g), ctypes.byref(ticket), _stream(stream))
+    del keep
+    ctx.check(rc, "r3_eval_submit_guarded")
+    return ticket.value
+
+
+def r3_eval_wait(ctx, ticket, raise_on_candidate=False, with_guard=False):
+    """Returns (status, EvalResult) of a submitted evaluation, or (status, EvalResult, GuardResult)
+    with with_guard; status is OK or ECANDIDATE."""
+    out, gout = EvalResult(), GuardResult()
+    rc = lib().r3_eval_wait(ctx.handle, ticket, ctypes.byref(out), ctypes.byref(gout))
+    if not (rc == ECANDIDATE and not raise_on_candidate):
+        ctx.check(rc, "r3_eval_wait")
+    return (rc, out, gout) if with_guard else (rc, out)
 
 
 def r3_writeset_regions(host_bitmap, nbytes, page_bytes, want_dirty):

@@ -569,10 +569,10 @@ static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pro
   return eval_collect(ctx, ctx->lanes[0], host_out, host_guard_out);
 }
 
-int r3_eval_submit(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
-                   const r3_table* check_tbl, const void* d_epilogue, void* d_live, r3_launch_fn launch,
-                   void* user, uint32_t warmup, uint32_t reps, uint32_t compare_policy,
-                   r3_region_result* d_regions, uint32_t* ticket_out, void* stream) {
+static int submit_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
+                       const r3_table* check_tbl, const void* d_epilogue, void* d_live, r3_launch_fn launch,
+                       void* user, uint32_t warmup, uint32_t reps, uint32_t compare_policy,
+                       r3_region_result* d_regions, const r3_guard* guard, uint32_t* ticket_out, void* stream) {
   if (ctx == nullptr) return R3_EINVAL;
   if (ticket_out == nullptr) return fail(ctx, R3_EINVAL, "pointer is NULL");
   *ticket_out = 0;
@@ -581,18 +581,35 @@ int r3_eval_submit(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prolo
     if (!ctx->lanes[i].busy) lane = i;
   if (lane == 0) return fail(ctx, R3_ENOSPC, "R3_MAX_INFLIGHT evaluations are in flight already");
   int rc = eval_enqueue(ctx, ctx->lanes[lane], restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, launch,
-                        user, warmup, reps, compare_policy, d_regions, nullptr, 1, 0, true, stream);
+                        user, warmup, reps, compare_policy, d_regions, guard, 1, 0, true, stream);
   if (rc == R3_OK) *ticket_out = lane;
   return rc;
 }
 
-int r3_eval_wait(r3_ctx* ctx, uint32_t ticket, r3_eval_result* host_out) {
+int r3_eval_submit(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
+                   const r3_table* check_tbl, const void* d_epilogue, void* d_live, r3_launch_fn launch,
+                   void* user, uint32_t warmup, uint32_t reps, uint32_t compare_policy,
+                   r3_region_result* d_regions, uint32_t* ticket_out, void* stream) {
+  return submit_impl(ctx, restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, launch, user, warmup, reps,
+                     compare_policy, d_regions, nullptr, ticket_out, stream);
+}
+
+int r3_eval_submit_guarded(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
+                           const r3_table* check_tbl, const void* d_epilogue, void* d_live,
+                           r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
+                           uint32_t compare_policy, r3_region_result* d_regions, const r3_guard* guard,
+                           uint32_t* ticket_out, void* stream) {
+  return submit_impl(ctx, restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, launch, user, warmup, reps,
+                     compare_policy, d_regions, guard, ticket_out, stream);
+}
+
+int r3_eval_wait(r3_ctx* ctx, uint32_t ticket, r3_eval_result* host_out, r3_guard_result* host_guard_out) {
   if (ctx == nullptr) return R3_EINVAL;
   ctx->err.clear();
   if (host_out == nullptr) return fail(ctx, R3_EINVAL, "pointer is NULL");
   if (ticket == 0 || ticket > R3_MAX_INFLIGHT || !ctx->lanes[ticket].busy)
     return fail(ctx, R3_EINVAL, "no evaluation in flight under this ticket");
-  return eval_collect(ctx, ctx->lanes[ticket], host_out, nullptr);
+  return eval_collect(ctx, ctx->lanes[ticket], host_out, host_guard_out);
 }
 
 int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,

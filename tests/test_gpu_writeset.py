@@ -176,3 +176,112 @@ def test_jacobi_writeset_is_the_interior_of_out(env, oracle):
         assert out.passed == int(not bug)
         exp, _ = oracle.compare(oracle.make_table([c["check_rows"][1]]), host(d_live), host(d_epi))
         assert r3.results_to_numpy(d_regions, 1).tobytes() == exp.tobytes()
+
+
+def test_guarded_evaluations_in_flight(env, oracle):
+    """r3_eval_submit_guarded: write-set replays of all Jacobi variants in flight together give the
+    verdicts of the one-at-a-time calls; a candidate that writes outside the write-set fails its
+    guard, so does the evaluation queued behind it, and after the heal that one passes."""
+    r3, wl, ctx, torch = env
+    n = 64
+    c = ri.jacobi(n)
+    A = c["arena_bytes"]
+    full = r3.Table(ctx, c["restore_rows"], A)
+    d_live = dev(torch, c["prologue"])
+    d_pro = torch.empty(A, dtype=torch.uint8, device="cuda:0")
+    d_epi = torch.empty(A, dtype=torch.uint8, device="cuda:0")
+    d_bm = torch.zeros(r3.bitmap_words(A, 4096), dtype=torch.int64, device="cuda:0")
+    r3.r3_record(ctx, full, d_live, wl.jacobi_launch(), wl.jacobi_args(c, 256, 1, 0), d_pro, d_epi, 4096, d_bm)
+    bm = host(d_bm).view(np.uint64)
+    dirty = r3.r3_writeset_regions(bm, A, 4096, 1)
+    clean = r3.r3_writeset_regions(bm, A, 4096, 0)
+    ws_tbl, guard_tbl = r3.Table(ctx, dirty, A), r3.Table(ctx, clean, A)
+    check_rows = [c["check_rows"][1]]
+    check = r3.Table(ctx, check_rows, A)
+    d_expected = torch.zeros(guard_tbl.n, dtype=torch.int64, device="cuda:0")
+    d_scratch = torch.zeros(guard_tbl.n, dtype=torch.int64, device="cuda:0")
+    r3.r3_checksum(ctx, guard_tbl, d_pro, d_expected)
+    torch.cuda.synchronize()
+    pro_h, epi_h = host(d_pro), host(d_epi)
+    exp_cs = oracle.checksum(oracle.make_table(clean), pro_h)
+    bufs = [torch.zeros(40, dtype=torch.uint8, device="cuda:0") for _ in range(8)]
+
+    # every variant, one at a time, against the oracle on the bytes it left
+    d_live.copy_(d_pro)
+    alone = []
+    for block, unroll, bug in ri.JACOBI_VARIANTS:
+        rc, out, g = r3.r3_eval_candidate_guarded(ctx, ws_tbl, d_pro, check, d_epi, d_live, wl.jacobi_launch(),
+                                                  wl.jacobi_args(c, block, unroll, bug), 0, 2, r3.EVERY,
+                                                  bufs[0], guard_tbl, d_expected, d_scratch, every=1)
+        exp, _ = oracle.compare(oracle.make_table(check_rows), host(d_live), epi_h)
+        assert r3.results_to_numpy(bufs[0], 1).tobytes() == exp.tobytes()
+        assert (g.checks, g.failed_checks) == (2, 0)
+        alone.append((exp, out))
+    # the same eight, all in flight
+    args = [wl.jacobi_args(c, block, unroll, bug) for block, unroll, bug in ri.JACOBI_VARIANTS]
+    tickets = [r3.r3_eval_submit_guarded(ctx, ws_tbl, d_pro, check, d_epi, d_live, wl.jacobi_launch(), a,
+                                         0, 2, r3.EVERY, bufs[i], guard_tbl, d_expected, d_scratch, every=1)
+               for i, a in enumerate(args)]
+    for i in reversed(range(8)):
+        rc, out, g = r3.r3_eval_wait(ctx, tickets[i], with_guard=True)
+        exp, exp_out = alone[i]
+        assert rc == r3.OK and (g.checks, g.failed_checks, g.healed) == (2, 0, 0)
+        assert r3.results_to_numpy(bufs[i], 1).tobytes() == exp.tobytes()
+        for f in ("total_mismatch", "first_region", "first_index", "passed", "max_abs_err", "max_rel_err"):
+            assert getattr(out, f) == getattr(exp_out, f), (i, f)
+
+    # a stray write outside the write-set (last byte of the `in` grid), then a good candidate behind it
+    stray_at = c["in_off"] + c["grid_bytes"] - 1
+    good = wl.jacobi_args(c, 128, 1, 0)
+    launch = wl.lib().r3w_jacobi_launch
+    launch.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    stray_value = int(pro_h[stray_at]) ^ 0x55
+
+    def gpu_stray(live_ptr, stream):
+        rc = launch(ctypes.addressof(good), live_ptr, stream)
+        d_live[stray_at] = stray_value
+        return rc
+    out_off, gb = c["out_off"], c["grid_bytes"]
+    # what a correct sweep leaves in `out`
+    rc, out, g = r3.r3_eval_candidate_guarded(ctx, ws_tbl, d_pro, check, d_epi, d_live, wl.jacobi_launch(), good,
+                                              0, 1, r3.EVERY, bufs[0], guard_tbl, d_expected, d_scratch, every=0)
+    assert out.passed == 1
+    good_out = host(d_live)[out_off:out_off + gb].copy()
+
+    def cpu_stray(live):
+        live[out_off:out_off + gb] = good_out
+        live[stray_at] = stray_value
+        return 0
+
+    def cpu_good(live):
+        live[out_off:out_off + gb] = good_out
+        return 0
+    t_a = r3.r3_eval_submit_guarded(ctx, ws_tbl, d_pro, check, d_epi, d_live, gpu_stray, None, 0, 1, r3.EVERY,
+                                    bufs[0], guard_tbl, d_expected, d_scratch, every=0, heal_tbl=full)
+    t_b = r3.r3_eval_submit_guarded(ctx, ws_tbl, d_pro, check, d_epi, d_live, wl.jacobi_launch(), good, 0, 1,
+                                    r3.EVERY, bufs[1], guard_tbl, d_expected, d_scratch, every=0, heal_tbl=full)
+    rc_a, out_a, g_a = r3.r3_eval_wait(ctx, t_a, with_guard=True)
+    rc_b, out_b, g_b = r3.r3_eval_wait(ctx, t_b, with_guard=True)
+    # the oracle's account of the same sequence: A and B run before any heal, then the heal
+    otab = dict(guard_tbl=oracle.make_table(clean), guard_expected=exp_cs, guard_every=0)
+    live_h = pro_h.copy()
+    exp_a = oracle.eval_candidate(oracle.make_table(dirty), pro_h, oracle.make_table(check_rows), epi_h, live_h,
+                                  cpu_stray, 0, 1, oracle.EVERY, heal_tbl=None, **otab)
+    exp_b = oracle.eval_candidate(oracle.make_table(dirty), pro_h, oracle.make_table(check_rows), epi_h, live_h,
+                                  cpu_good, 0, 1, oracle.EVERY, heal_tbl=None, **otab)
+    for (rc, out, g), exp in (((rc_a, out_a, g_a), exp_a), ((rc_b, out_b, g_b), exp_b)):
+        assert rc == r3.OK and out.total_mismatch == exp["total_mismatch"] == 0
+        assert out.passed == exp["pass"] == 0
+        assert (g.checks, g.failed_checks, g.changed_regions, g.first_region) == (
+            exp["guard"]["checks"], exp["guard"]["failed_checks"], exp["guard"]["changed_regions"],
+            exp["guard"]["first_region"])
+        assert g.failed_checks == 1 and g.healed == 1
+    # healed: live memory is the recorded prologue again, and B passes when submitted again
+    oracle.restore(oracle.make_table(c["restore_rows"]), pro_h, live_h)
+    assert (host(d_live) == live_h).all()
+    t_b = r3.r3_eval_submit_guarded(ctx, ws_tbl, d_pro, check, d_epi, d_live, wl.jacobi_launch(), good, 0, 1,
+                                    r3.EVERY, bufs[1], guard_tbl, d_expected, d_scratch, every=0, heal_tbl=full)
+    rc_b, out_b, g_b = r3.r3_eval_wait(ctx, t_b, with_guard=True)
+    exp_b = oracle.eval_candidate(oracle.make_table(dirty), pro_h, oracle.make_table(check_rows), epi_h, live_h,
+                                  cpu_good, 0, 1, oracle.EVERY, heal_tbl=None, **otab)
+    assert rc_b == r3.OK and out_b.passed == exp_b["pass"] == 1 and g_b.failed_checks == 0
