@@ -391,3 +391,63 @@ def test_compare_many_regions_full_size(env, oracle):
     assert_results_equal(got_res, exp_res, "regions")
     assert_results_equal(got_sum, exp_sum, "summary")
     assert int(got_sum[0]["total_mismatch"]) > 1000
+
+
+def test_compare_near_tied_relative_errors(env, oracle):
+    """The largest relative error of a region when many elements are within a few units in the
+    last place of it, for tiny, ordinary and huge recorded values and relative errors above one:
+    the kernel divides only where the running maximum can still grow, and must not lose the
+    element that carries it."""
+    r3, ctx, torch = env
+    rng = np.random.default_rng(4711)
+    n = 150000
+    parts = []   # (dtype, golden bits as uint8, live bits as uint8)
+
+    def f64_case(scale_lo, scale_hi, rel, spread_ulps):
+        g = (rng.choice([-1.0, 1.0], n) * rng.uniform(1, 2, n) * np.exp2(rng.integers(scale_lo, scale_hi + 1, n)))
+        g = g.astype("<f8")
+        # relative offsets that differ from `rel` by a few units in its last place
+        k = rng.integers(-spread_ulps, spread_ulps + 1, n)
+        r = (np.float64(rel).view(np.int64) + k).view(np.float64)
+        c = (g * (1.0 + r)).astype("<f8")
+        parts.append((ri.F64, g.view(np.uint8), c.view(np.uint8)))
+
+    f64_case(-20, 20, 1e-3, 8)          # ordinary magnitudes
+    f64_case(-1070, -1010, 1e-3, 8)     # recorded values so small that gate * |G| is subnormal
+    f64_case(900, 1000, 1e-3, 8)        # huge values
+    f64_case(-5, 5, 3.0, 4)             # relative errors above one
+    f64_case(-1022, 1000, 2.0 ** -40, 2)  # the whole exponent range at once
+    # fp32 and bf16: the same idea with the spread applied to the live bit patterns
+    g32 = (rng.standard_normal(n) * np.exp2(rng.integers(-100, 100, n))).astype("<f4")
+    c32 = (g32.astype(np.float64) * (1 + 1e-3)).astype("<f4")
+    c32 = (c32.view(np.int32) + rng.integers(-1, 2, n).astype(np.int32)).view("<f4")
+    parts.append((ri.F32, g32.view(np.uint8), c32.view(np.uint8)))
+    gb = ri.f32_to_bf16_bits(rng.standard_normal(n) * np.exp2(rng.integers(-60, 60, n))).astype(np.uint16)
+    cb = (gb.astype(np.int32) + rng.integers(-2, 3, n)).astype(np.uint16)
+    parts.append((ri.BF16, gb.view(np.uint8), cb.view(np.uint8)))
+    gi = rng.integers(-(1 << 31), 1 << 31, n).astype("<i4")
+    ci = (gi.astype(np.int64) + rng.integers(-3, 4, n)).clip(-(1 << 31), (1 << 31) - 1).astype("<i4")
+    parts.append((ri.I32, gi.view(np.uint8), ci.view(np.uint8)))
+
+    rows, at = [], 0
+    for i, (dt, pg, _) in enumerate(parts):
+        rows.append((at, pg.size, dt, ri.TOL if i % 2 == 0 else ri.BITWISE, 1e-3, 0.0))
+        at += (pg.size + 255) // 256 * 256
+    gold, live = np.zeros(at, np.uint8), np.zeros(at, np.uint8)
+    for (off, nb, *_), (_, pg, pc) in zip(rows, parts):
+        gold[off:off + nb] = pg
+        live[off:off + nb] = pc
+    exp_res, exp_sum = oracle.compare(oracle.make_table(rows), live, gold)
+    assert (exp_res["max_rel_err"][:5] > 0).all() and np.isfinite(exp_res["max_rel_err"]).all()
+    res, summ = run_compare(r3, ctx, torch, rows, dev(torch, live), dev(torch, gold), at)
+    assert_results_equal(res, exp_res, "near-tied relative errors")
+    assert_results_equal(summ, exp_sum, "summary")
+    # the same data in the opposite element order: the maxima cannot depend on who comes first
+    gold_r, live_r = np.zeros(at, np.uint8), np.zeros(at, np.uint8)
+    for (off, nb, dt, *_), (_, pg, pc) in zip(rows, parts):
+        es = ri.ELEM_SIZE[dt]
+        gold_r[off:off + nb] = pg.reshape(-1, es)[::-1].reshape(-1)
+        live_r[off:off + nb] = pc.reshape(-1, es)[::-1].reshape(-1)
+    res_r, _ = run_compare(r3, ctx, torch, rows, dev(torch, live_r), dev(torch, gold_r), at)
+    for name in ("mismatch_count", "max_abs_err", "max_rel_err"):
+        assert (res_r[name].view(np.uint64) == exp_res[name].view(np.uint64)).all(), name
