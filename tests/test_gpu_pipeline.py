@@ -263,3 +263,53 @@ def test_several_units_resident(env, oracle):
         collect()
         done += 1
     assert done == len(work)
+
+
+def test_side_stream(env, oracle):
+    """Everything is enqueued on the stream the caller names: a replay on a second stream (default
+    priority) gives the oracle's results, also while the default stream is busy with other work."""
+    r3, wl, ctx, torch = env
+    c = ri.jacobi(40)
+    A = c["arena_bytes"]
+    side = torch.cuda.Stream()
+    tbl = r3.Table(ctx, c["restore_rows"], A)
+    chk = r3.Table(ctx, c["check_rows"], A)
+    d_live = dev(torch, c["prologue"])
+    d_pro = torch.empty(A, dtype=torch.uint8, device="cuda:0")
+    d_epi = torch.empty(A, dtype=torch.uint8, device="cuda:0")
+    nreg = len(c["check_rows"])
+    d_regions = torch.zeros(40 * nreg, dtype=torch.uint8, device="cuda:0")
+    d_cs = torch.zeros(len(c["restore_rows"]), dtype=torch.int64, device="cuda:0")
+    torch.cuda.synchronize()
+    busy = torch.empty(64 << 20, dtype=torch.uint8, device="cuda:0")
+    r3.r3_record(ctx, tbl, d_live, wl.jacobi_launch(), wl.jacobi_args(c, 64, 1, 0), d_pro, d_epi, 4096,
+                 None, None, None, None, stream=side)
+    epi = host(d_epi)
+    for i, (block, unroll, bug) in enumerate(ri.JACOBI_VARIANTS):
+        busy.fill_(i)                       # unrelated work on the default stream
+        args = wl.jacobi_args(c, block, unroll, bug)
+        if i % 2 == 0:
+            rc, out = r3.r3_eval_candidate(ctx, tbl, d_pro, chk, d_epi, d_live, wl.jacobi_launch(), args,
+                                           1, 2, r3.EVERY, d_regions, stream=side)
+        else:
+            t = r3.r3_eval_submit(ctx, tbl, d_pro, chk, d_epi, d_live, wl.jacobi_launch(), args,
+                                  1, 2, r3.EVERY, d_regions, stream=side)
+            rc, out = r3.r3_eval_wait(ctx, t)
+        assert rc == r3.OK
+        side.synchronize()
+        exp_res, exp_sum = oracle.compare(oracle.make_table(c["check_rows"]), host(d_live), epi)
+        assert_results_equal(r3.results_to_numpy(d_regions, nreg), exp_res, "variant %d" % i)
+        assert out.total_mismatch == int(exp_sum[0]["total_mismatch"]) and out.passed == int(not bug)
+    # the asynchronous calls: nothing is waited for until the caller does
+    d_sum = torch.zeros(40, dtype=torch.uint8, device="cuda:0")
+    torch.cuda.synchronize()                # d_sum's fill ran on the default stream
+    r3.r3_restore(ctx, tbl, d_pro, d_live, stream=side)
+    r3.r3_checksum(ctx, tbl, d_live, d_cs, stream=side)
+    r3.r3_compare(ctx, chk, d_live, d_epi, d_regions, d_sum, stream=side)
+    side.synchronize()
+    pro = host(d_pro)
+    assert (host(d_live) == pro).all()
+    assert (host(d_cs).view(np.uint64) == oracle.checksum(oracle.make_table(c["restore_rows"]), pro)).all()
+    exp_res, exp_sum = oracle.compare(oracle.make_table(c["check_rows"]), pro, epi)
+    assert_results_equal(r3.results_to_numpy(d_regions, nreg), exp_res, "restored state against the epilogue")
+    assert_results_equal(r3.summary_to_numpy(d_sum), exp_sum, "summary")
