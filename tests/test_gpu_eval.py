@@ -315,3 +315,51 @@ def test_large_snapshot_full_size(env, oracle):
         assert_results_equal(got[r:r + 1], exp, "region %d" % r)
         print("region", r, "oracle parity ok", flush=True)
         del live_h, gold_h
+
+
+def test_most_replays_one_evaluation_takes(env, oracle):
+    """R3_MAX_REPLAYS replays in one evaluation, validated after each: the verdict is the worst
+    replay's count, the region results are the last replay's."""
+    r3, wl, ctx, torch = env
+    rng = np.random.default_rng(99)
+    n = 1 << 14
+    pro = rng.integers(0, 256, size=n, dtype=np.uint8)
+    epi = (pro + 1).astype(np.uint8)
+    rows = [(0, n, ri.U8, ri.BITWISE, 0, 0)]
+    t = r3.Table(ctx, rows, n)
+    d_pro, d_epi = dev(torch, pro), dev(torch, epi)
+    d_live = torch.zeros(n, dtype=torch.uint8, device="cuda:0")
+    d_regions = torch.zeros(40, dtype=torch.uint8, device="cuda:0")
+    total = 1024
+    state = {"k": 0}
+
+    def gpu_candidate(live_ptr, stream):
+        d_live.add_(1)
+        if state["k"] == 700:
+            d_live[5:9] = 0
+        if state["k"] == total - 1:
+            d_live[100] ^= 0xFF
+        state["k"] += 1
+        return 0
+
+    def cpu_candidate(live):
+        live += 1
+        if state["k"] == 700:
+            live[5:9] = 0
+        if state["k"] == total - 1:
+            live[100] ^= 0xFF
+        state["k"] += 1
+        return 0
+    rc, out = r3.r3_eval_candidate(ctx, t, d_pro, t, d_epi, d_live, gpu_candidate, None, 24, total - 24,
+                                   r3.EVERY, d_regions)
+    state["k"] = 0
+    live = np.zeros(n, np.uint8)
+    exp = oracle.eval_candidate(oracle.make_table(rows), pro, oracle.make_table(rows), epi, live, cpu_candidate,
+                                24, total - 24, oracle.EVERY)
+    assert rc == r3.OK and state["k"] == total
+    assert_results_equal(r3.results_to_numpy(d_regions, 1), exp["regions"], "last replay")
+    assert (out.total_mismatch, out.passed, out.first_index) == (exp["total_mismatch"], 0, exp["first_index"])
+    assert out.total_mismatch >= 1 and int(exp["regions"][0]["mismatch_count"]) == 1
+    assert (host(d_live) == live).all()
+    times = ctx.last_times()
+    assert len(times) == total - 24 and min(times) > 0

@@ -451,3 +451,44 @@ def test_compare_near_tied_relative_errors(env, oracle):
     res_r, _ = run_compare(r3, ctx, torch, rows, dev(torch, live_r), dev(torch, gold_r), at)
     for name in ("mismatch_count", "max_abs_err", "max_rel_err"):
         assert (res_r[name].view(np.uint64) == exp_res[name].view(np.uint64)).all(), name
+
+
+def test_twenty_thousand_tiny_regions(env, oracle):
+    """A table of 20000 regions of 0..64 bytes (one tile each at most): restore, checksum and
+    compare against the oracle; the summary comes from a pass over 20000 region results."""
+    r3, ctx, torch = env
+    rng = np.random.default_rng(2024)
+    n = 20000
+    dts = [ri.U8, ri.F32, ri.F64, ri.I32, ri.BF16]
+    rows, at = [], 0
+    for i in range(n):
+        dt = dts[int(rng.integers(0, 5))]
+        es = ri.ELEM_SIZE[dt]
+        nb = int(rng.integers(0, 64 // es + 1)) * es
+        at = (at + es - 1) // es * es + int(rng.integers(0, 3)) * es
+        rows.append((at, nb, dt, ri.TOL if i % 3 else ri.BITWISE, 1e-3, 1e-6))
+        at += nb
+    A = (at + 255) // 256 * 256
+    snap = rng.integers(0, 256, size=A, dtype=np.uint8)
+    live = snap.copy()
+    idx = rng.choice(A, size=A // 200, replace=False)
+    live[idx] ^= rng.integers(1, 256, size=idx.size, dtype=np.uint8)
+    otbl = oracle.make_table(rows)
+    tbl = r3.Table(ctx, rows, A)
+    # restore into a canary-filled arena
+    d_snap, d_dst = dev(torch, snap), torch.full((A,), 0xEE, dtype=torch.uint8, device="cuda:0")
+    r3.r3_restore(ctx, tbl, d_snap, d_dst)
+    exp_dst = np.full(A, 0xEE, np.uint8)
+    oracle.restore(otbl, snap, exp_dst)
+    assert (host(d_dst) == exp_dst).all()
+    # checksums
+    d_cs = torch.zeros(n, dtype=torch.int64, device="cuda:0")
+    r3.r3_checksum(ctx, tbl, d_snap, d_cs)
+    torch.cuda.synchronize()
+    assert (host(d_cs).view(np.uint64) == oracle.checksum(otbl, snap)).all()
+    # compare
+    exp_res, exp_sum = oracle.compare(otbl, live, snap)
+    got_res, got_sum = run_compare(r3, ctx, torch, rows, dev(torch, live), d_snap, A)
+    assert_results_equal(got_res, exp_res, "regions")
+    assert_results_equal(got_sum, exp_sum, "summary")
+    assert int(got_sum[0]["total_mismatch"]) > 100
