@@ -33,8 +33,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # Valid only for the kernel source they were taken with: reported as null otherwise.
 COUNTERS = {
     "kernels_sha256_16": "c42d24e1274cac2b",
-    "jacobi": {"restore": 541103280, "validate": 269491056},
-    "large_snapshot": {"restore": 68754927113, "validate": 68734160951},
+    "jacobi": {"restore": 541102311, "validate": 269491067},
+    "large_snapshot": {"restore": 68755014062, "validate": 68734155091},
 }
 
 
