@@ -478,7 +478,7 @@ def large_leg(r3, wl, ctx, torch):
 def main():
     a = parse()
     if a.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused)" % a.gpus,
+        print("bench.py measures one GPU: the library has no multi-GPU path (--gpus %d refused)" % a.gpus,
               file=sys.stderr)
         sys.exit(2)
     import torch
