@@ -54,7 +54,10 @@ def run_compare(r3, ctx, torch, rows, live, golden, arena_bytes):
 # checksum and restore on many small regions (the many-regions workload shape, reduced and full)
 # ----------------------------------------------------------------------------------------
 @pytest.mark.parametrize("n_regions,max_bytes,align", [(300, 1 << 18, 256), (300, 1 << 17, 1),
-                                                       (64, 1 << 21, 16), (4096, 1 << 20, 256)])
+                                                       (64, 1 << 21, 16), (4096, 1 << 20, 256),
+                                                       # few regions, large and small, unaligned
+                                                       (16, 1 << 22, 1), (12, 1 << 16, 1), (5, 1 << 24, 16),
+                                                       (1, 1 << 20, 1), (17, 1 << 18, 1)])
 def test_checksum_and_restore_many_regions(env, oracle, n_regions, max_bytes, align):
     r3, ctx, torch = env
     c = ri.many_regions(n_regions=n_regions, max_bytes=max_bytes, align=align, seed=1003 + align)
@@ -492,3 +495,34 @@ def test_twenty_thousand_tiny_regions(env, oracle):
     assert_results_equal(got_res, exp_res, "regions")
     assert_results_equal(got_sum, exp_sum, "summary")
     assert int(got_sum[0]["total_mismatch"]) > 100
+
+
+def test_restore_few_regions_with_empty_and_tiny_ones(env, oracle):
+    """Restore of small tables under several copy shapes: empty regions at the start, in the middle
+    and at the end, regions shorter than a copy unit, regions that start one element before or
+    after a unit boundary, all element sizes."""
+    r3, ctx, torch = env
+    rng = np.random.default_rng(77)
+    A = 1 << 20
+    snap = rng.integers(0, 256, size=A, dtype=np.uint8)
+    tables = [
+        [(0, 0, ri.U8, 0, 0, 0), (1023, 1, ri.U8, 0, 0, 0), (1024, 0, ri.F64, 0, 0, 0), (1025, 1023, ri.U8, 0, 0, 0),
+         (4096 - 2, 2050, ri.BF16, 0, 0, 0), (8192 + 4, 1020, ri.I32, 0, 0, 0), (16384 - 8, 24, ri.F64, 0, 0, 0),
+         (32768, 3000, ri.F32, 0, 0, 0), (65536 + 1, 70001, ri.U8, 0, 0, 0), (A - 8, 8, ri.F64, 0, 0, 0),
+         (A, 0, ri.U8, 0, 0, 0)],
+        [(5, 1, ri.U8, 0, 0, 0)],
+        [(0, A, ri.U8, 0, 0, 0)],
+        [(8, A - 16, ri.F64, 0, 0, 0)],
+        [(0, 0, ri.F32, 0, 0, 0), (0, 0, ri.F32, 0, 0, 0), (2, 6, ri.BF16, 0, 0, 0)],
+    ]
+    for unit, block in ((1024, 64), (4096, 256), (1 << 20, 128), (1024, 64)):
+        assert r3.lib().r3_tune_copy(unit, block) == r3.OK
+        for rows in tables:
+            tbl = r3.Table(ctx, rows, A)
+            d_live = torch.full((A,), 0xEE, dtype=torch.uint8, device="cuda:0")
+            r3.r3_restore(ctx, tbl, dev(torch, snap), d_live)
+            exp = np.full(A, 0xEE, np.uint8)
+            oracle.restore(oracle.make_table(rows), snap, exp)
+            got = host(d_live)
+            assert (got == exp).all(), (unit, rows[:3], np.flatnonzero(got != exp)[:8])
+    assert r3.lib().r3_tune_copy(0, 0) == r3.OK
