@@ -57,8 +57,8 @@ typedef enum {
   R3_ECANDIDATE = -7  /* the candidate's launch callback or its kernel launch failed       */
 } r3_status;
 
-/* Element types of a region: 1, 4, 8, 4, 2 bytes. */
-typedef enum { R3_U8 = 0, R3_F32 = 1, R3_F64 = 2, R3_I32 = 3, R3_BF16 = 4 } r3_dtype;
+/* Element types of a region: 1, 4, 8, 4, 2, 2 bytes (R3_F16 = IEEE binary16). */
+typedef enum { R3_U8 = 0, R3_F32 = 1, R3_F64 = 2, R3_I32 = 3, R3_BF16 = 4, R3_F16 = 5 } r3_dtype;
 
 /* Section V-C: bitwise equality is the default criterion; tolerances apply only
  * to regions the user marks (the role of the paper's `annotate`). */

@@ -24,7 +24,7 @@
 #include <string.h>
 
 enum { O_OK = 0, O_EINVAL = -1, O_EALIGN = -2, O_ERANGE = -3, O_EOVERLAP = -4 };
-enum { O_U8 = 0, O_F32 = 1, O_F64 = 2, O_I32 = 3, O_BF16 = 4 };
+enum { O_U8 = 0, O_F32 = 1, O_F64 = 2, O_I32 = 3, O_BF16 = 4, O_F16 = 5 };
 enum { O_BITWISE = 0, O_TOL = 1 };
 
 typedef struct {
@@ -52,6 +52,7 @@ static uint64_t elem_size(uint32_t dtype) {
     case O_F64: return 8;
     case O_I32: return 4;
     case O_BF16: return 2;
+    case O_F16: return 2;
     default: return 0;
   }
 }
@@ -147,6 +148,24 @@ static void load_elem(const uint8_t* base, uint32_t dtype, uint64_t i, uint64_t*
       *bits = h;
       *val = f32_from_bits((uint32_t)h << 16); /* bf16 is the top half of a binary32 */
       *nonfinite = isnan(*val) || isinf(*val);
+      break;
+    }
+    case O_F16: {
+      /* IEEE binary16: 1 sign bit, 5 exponent bits (bias 15), 10 fraction bits.  Every
+       * value is exactly representable in binary64. */
+      uint16_t h;
+      memcpy(&h, base + 2 * i, 2);
+      *bits = h;
+      int sign = h >> 15, e = (h >> 10) & 31, m = h & 1023;
+      if (e == 31) {
+        *val = m ? NAN : INFINITY;
+        *nonfinite = 1;
+      } else if (e == 0) {
+        *val = ldexp((double)m, -24); /* zero and subnormals: m * 2^-10 * 2^-14 */
+      } else {
+        *val = ldexp((double)(1024 + m), e - 25); /* (1 + m/1024) * 2^(e-15) */
+      }
+      if (sign) *val = -*val;
       break;
     }
     default: { /* O_F64 */

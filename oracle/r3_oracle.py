@@ -20,12 +20,12 @@ _LIB = os.path.join(_HERE, "libr3_oracle.so")
 
 # status codes, element types, modes, policies (interface constants)
 OK, EINVAL, EALIGN, ERANGE, EOVERLAP = 0, -1, -2, -3, -4
-U8, F32, F64, I32, BF16 = 0, 1, 2, 3, 4
+U8, F32, F64, I32, BF16, F16 = 0, 1, 2, 3, 4, 5
 BITWISE, TOL = 0, 1
 EVERY, FIRST, LAST = 0, 1, 2
 NO_INDEX = 0xFFFFFFFFFFFFFFFF
 NO_REGION = 0xFFFFFFFF
-ELEM_SIZE = {U8: 1, F32: 4, F64: 8, I32: 4, BF16: 2}
+ELEM_SIZE = {U8: 1, F32: 4, F64: 8, I32: 4, BF16: 2, F16: 2}
 
 REGION_DTYPE = np.dtype(
     [("offset", "<u8"), ("bytes", "<u8"), ("dtype", "<u4"), ("mode", "<u4"),

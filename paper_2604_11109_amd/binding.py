@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libr3.so")
 # status codes
 OK, EINVAL, EALIGN, ERANGE, EOVERLAP, ENOSPC, EHIP, ECANDIDATE = 0, -1, -2, -3, -4, -5, -6, -7
 # element types, modes, policies
-U8, F32, F64, I32, BF16 = 0, 1, 2, 3, 4
+U8, F32, F64, I32, BF16, F16 = 0, 1, 2, 3, 4, 5
 BITWISE, TOL = 0, 1
 EVERY, FIRST, LAST = 0, 1, 2
 NO_INDEX = 0xFFFFFFFFFFFFFFFF

@@ -225,7 +225,7 @@ __device__ __forceinline__ void copy_span(const uint8_t* src, uint8_t* dst, uint
 }
 
 __device__ __forceinline__ uint32_t elem_size_dev(uint32_t dtype) {
-  return dtype == R3_U8 ? 1u : dtype == R3_BF16 ? 2u : dtype == R3_F64 ? 8u : 4u;
+  return dtype == R3_U8 ? 1u : (dtype == R3_BF16 || dtype == R3_F16) ? 2u : dtype == R3_F64 ? 8u : 4u;
 }
 
 // Copy kernels run best here as very many short wavefronts that each move 1 KiB (one
@@ -397,12 +397,18 @@ struct ElemKind {
   double rtol, atol;
 };
 
+// binary16 -> binary64 (exact): through the hardware conversion to binary32.
+__device__ __forceinline__ double f16_to_f64(uint32_t bits) {
+  return (double)(float)__builtin_bit_cast(_Float16, (uint16_t)bits);
+}
+
 __device__ __forceinline__ double to_f64(uint64_t bits, uint32_t dtype) {
   switch (dtype) {  // uniform across the wavefront: a scalar branch
     case R3_U8: return (double)(uint32_t)bits;
     case R3_I32: return (double)(int32_t)(uint32_t)bits;
     case R3_F32: return (double)__uint_as_float((uint32_t)bits);
     case R3_BF16: return (double)__uint_as_float((uint32_t)bits << 16);
+    case R3_F16: return f16_to_f64((uint32_t)bits);
     default: return bits_d(bits);
   }
 }
@@ -486,6 +492,7 @@ template <> struct Elem<R3_F32>  { static constexpr int size = 4; static constex
 template <> struct Elem<R3_F64>  { static constexpr int size = 8; static constexpr bool is_float = true; };
 template <> struct Elem<R3_I32>  { static constexpr int size = 4; static constexpr bool is_float = false; };
 template <> struct Elem<R3_BF16> { static constexpr int size = 2; static constexpr bool is_float = true; };
+template <> struct Elem<R3_F16>  { static constexpr int size = 2; static constexpr bool is_float = true; };
 
 template <int DT>
 __device__ __forceinline__ double to_f64_t(uint64_t bits) {
@@ -493,6 +500,7 @@ __device__ __forceinline__ double to_f64_t(uint64_t bits) {
   if (DT == R3_I32) return (double)(int32_t)(uint32_t)bits;
   if (DT == R3_F32) return (double)__uint_as_float((uint32_t)bits);
   if (DT == R3_BF16) return (double)__uint_as_float((uint32_t)bits << 16);
+  if (DT == R3_F16) return f16_to_f64((uint32_t)bits);
   return bits_d(bits);
 }
 
@@ -579,7 +587,8 @@ __device__ __forceinline__ bool differing_vec(u32x4 c, u32x4 g, uint32_t idx, co
     case R3_F32: return vec_both<R3_F32>(c, g, idx, k, a);
     case R3_F64: return vec_both<R3_F64>(c, g, idx, k, a);
     case R3_I32: return vec_both<R3_I32>(c, g, idx, k, a);
-    default: return vec_both<R3_BF16>(c, g, idx, k, a);
+    case R3_BF16: return vec_both<R3_BF16>(c, g, idx, k, a);
+    default: return vec_both<R3_F16>(c, g, idx, k, a);
   }
 }
 
@@ -711,7 +720,7 @@ __global__ __launch_bounds__(kBlock) void compare_kernel(TableDev t, const uint8
   ElemKind k;
   k.dtype = tv.dtype;
   k.es = elem_size_dev(tv.dtype);
-  k.is_float = tv.dtype == R3_F32 || tv.dtype == R3_F64 || tv.dtype == R3_BF16;
+  k.is_float = tv.dtype == R3_F32 || tv.dtype == R3_F64 || tv.dtype == R3_BF16 || tv.dtype == R3_F16;
   k.tol = tv.mode == R3_CMP_TOL;
   k.rtol = tv.rtol;
   k.atol = tv.atol;

@@ -21,6 +21,7 @@ uint32_t elem_size(uint32_t dtype) {
     case R3_F64: return 8;
     case R3_I32: return 4;
     case R3_BF16: return 2;
+    case R3_F16: return 2;
     default: return 0;
   }
 }

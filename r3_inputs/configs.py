@@ -11,9 +11,9 @@ Element type / mode codes are the interface constants of the region table.
 """
 import numpy as np
 
-U8, F32, F64, I32, BF16 = 0, 1, 2, 3, 4
+U8, F32, F64, I32, BF16, F16 = 0, 1, 2, 3, 4, 5
 BITWISE, TOL = 0, 1
-ELEM_SIZE = {U8: 1, F32: 4, F64: 8, I32: 4, BF16: 2}
+ELEM_SIZE = {U8: 1, F32: 4, F64: 8, I32: 4, BF16: 2, F16: 2}
 SEEDS = {"replay_small": 1001, "jacobi": 1002, "many_regions": 1003, "large_snapshot": 1004,
          "spmv": 1005}
 
@@ -304,9 +304,9 @@ def mixed_compare_case(seed, n_regions=24, max_bytes=300000, align=16, specials=
     arena that differs from it by bit-pattern steps, swapped values and special values."""
     rng = np.random.default_rng(seed)
     rows, at = [], 0
-    dts = [U8, F32, F64, I32, BF16]
+    dts = [U8, F32, F64, I32, BF16, F16]
     for r in range(n_regions):
-        dt = dts[r % 5] if r < 10 else int(rng.choice(dts))
+        dt = dts[r % 6] if r < 12 else int(rng.choice(dts))
         es = ELEM_SIZE[dt]
         kind = r % 6
         if kind == 0:
@@ -335,6 +335,8 @@ def mixed_compare_case(seed, n_regions=24, max_bytes=300000, align=16, specials=
             g = (rng.standard_normal(n) * np.exp(rng.uniform(-30, 30, n))).astype("<f8").view(np.uint64)
         elif dt == BF16:
             g = f32_to_bf16_bits(rng.standard_normal(n)).astype(np.uint64)
+        elif dt == F16:
+            g = (rng.standard_normal(n) * np.exp(rng.uniform(-8, 8, n))).astype("<f2").view(np.uint16).astype(np.uint64)
         elif dt == I32:
             g = rng.integers(0, 1 << 32, size=n, dtype=np.uint64)
         else:
@@ -353,8 +355,9 @@ def mixed_compare_case(seed, n_regions=24, max_bytes=300000, align=16, specials=
             hi = min(n, lo + int(rng.integers(1, 200)))
             c[lo:hi] = g[rng.integers(0, n, size=hi - lo)]
         # style 3: identical
-        if specials and dt in (F32, F64, BF16):
-            sp = {F32: [0x0, 0x80000000, 0x1, 0x7F800000, 0xFF800000, 0x7FC00000, 0x7FC00001, 0x00800000],
+        if specials and dt in (F32, F64, BF16, F16):
+            sp = {F16: [0x0, 0x8000, 0x1, 0x7C00, 0xFC00, 0x7E00, 0x7E01, 0x0400],
+                  F32: [0x0, 0x80000000, 0x1, 0x7F800000, 0xFF800000, 0x7FC00000, 0x7FC00001, 0x00800000],
                   BF16: [0x0, 0x8000, 0x1, 0x7F80, 0xFF80, 0x7FC0, 0x7FC1, 0x0080],
                   F64: [0x0, 1 << 63, 0x1, 0x7FF << 52, 0xFFF << 52, (0x7FF << 52) | (1 << 51),
                         0x7FEFFFFFFFFFFFFF, 0xFFEFFFFFFFFFFFFF]}[dt]

@@ -150,6 +150,9 @@ def _decode(dtype_name, raw):
     elif dtype_name == "bf16":
         bits = struct.unpack("<H", raw)[0]
         v = struct.unpack("<f", struct.pack("<I", bits << 16))[0]
+    elif dtype_name == "f16":
+        bits = struct.unpack("<H", raw)[0]
+        v = struct.unpack("<e", raw)[0]          # the struct module's own binary16 decoder
     else:
         bits = struct.unpack("<Q", raw)[0]
         v = struct.unpack("<d", raw)[0]
@@ -168,7 +171,7 @@ def _rn(x):
 
 def brute_compare(dtype_name, live, golden, mode_tol, rtol, atol):
     """Element-by-element validation in exact rationals, one rounding per operation."""
-    size = {"u8": 1, "i32": 4, "f32": 4, "bf16": 2, "f64": 8}[dtype_name]
+    size = {"u8": 1, "i32": 4, "f32": 4, "bf16": 2, "f16": 2, "f64": 8}[dtype_name]
     n = len(live) // size
     count, first, max_abs, max_rel = 0, M64, 0.0, 0.0
     for i in range(n):
@@ -200,8 +203,8 @@ def brute_compare(dtype_name, live, golden, mode_tol, rtol, atol):
     return count, first, max_abs, max_rel
 
 
-_DT = {"u8": 0, "f32": 1, "f64": 2, "i32": 3, "bf16": 4}
-_NP = {"u8": np.uint8, "f32": np.uint32, "f64": np.uint64, "i32": np.uint32, "bf16": np.uint16}
+_DT = {"u8": 0, "f32": 1, "f64": 2, "i32": 3, "bf16": 4, "f16": 5}
+_NP = {"u8": np.uint8, "f32": np.uint32, "f64": np.uint64, "i32": np.uint32, "bf16": np.uint16, "f16": np.uint16}
 
 
 def _bits_equal(a, b):
@@ -231,6 +234,9 @@ def _special_bits(dtype_name):
     if dtype_name == "bf16":
         return [0x0000, 0x8000, 0x0001, 0x807F, 0x0080, 0x7F7F, 0xFF7F, 0x7F80, 0xFF80, 0x7FC0,
                 0x7FC1, 0x3F80, 0x3F81, 0xBF80, 0x4000]
+    if dtype_name == "f16":
+        return [0x0000, 0x8000, 0x0001, 0x83FF, 0x0400, 0x7BFF, 0xFBFF, 0x7C00, 0xFC00, 0x7E00,
+                0x7E01, 0x3C00, 0x3C01, 0xBC00, 0x4000]
     if dtype_name == "f64":
         return [0x0, 0x8000000000000000, 0x1, 0x800FFFFFFFFFFFFF, 0x0010000000000000,
                 0x7FEFFFFFFFFFFFFF, 0xFFEFFFFFFFFFFFFF, 0x7FF0000000000000, 0xFFF0000000000000,
@@ -244,13 +250,15 @@ def _special_bits(dtype_name):
 def check_compare_bruteforce(api, seed=11, n=600):
     """Random + special values of every element type against the exact-rational restatement."""
     rng = np.random.default_rng(seed)
-    for dtype_name in ["f32", "bf16", "f64", "i32", "u8"]:
+    for dtype_name in ["f32", "bf16", "f16", "f64", "i32", "u8"]:
         npdt = np.dtype(_NP[dtype_name])
         sp = np.array(_special_bits(dtype_name), dtype=np.uint64)
         for mode_tol, rtol, atol in [(False, 0.0, 0.0), (True, 1e-5, 1e-7), (True, 0.0, 0.0),
                                      (True, 1e-2, 1e-3), (True, 0.5, 3.0)]:
-            if dtype_name in ("f32", "f64", "bf16"):
-                if dtype_name == "f64":
+            if dtype_name in ("f32", "f64", "bf16", "f16"):
+                if dtype_name == "f16":
+                    g = rng.standard_normal(n).astype("<f2").view(np.uint16)
+                elif dtype_name == "f64":
                     g = rng.standard_normal(n).astype("<f8").view(np.uint64)
                 elif dtype_name == "f32":
                     g = rng.standard_normal(n).astype("<f4").view(np.uint32)
@@ -284,6 +292,25 @@ def check_compare_bruteforce(api, seed=11, n=600):
             assert _bits_equal(float(res["max_rel_err"]), exp[3]), tag
             assert int(res["checksum"]) == brute_checksum(lb), tag
             assert int(summ["total_mismatch"]) == exp[0] and int(summ["pass"]) == int(exp[0] == 0)
+
+
+def check_f16_every_pattern(api):
+    """All 65536 binary16 patterns, each as a one-element region against +0: the absolute error is
+    the magnitude of the pattern's value, which numpy's float16 gives independently."""
+    pats = np.arange(65536, dtype=np.uint16)
+    ref = np.abs(pats.view(np.float16).astype(np.float64))
+    for lo in range(0, 65536, 4096):
+        chunk = pats[lo:lo + 4096]
+        live = chunk.view(np.uint8).copy()
+        gold = np.zeros_like(live)
+        tbl = api.make_table([(2 * i, 2, _DT["f16"], api.BITWISE, 0, 0) for i in range(chunk.size)])
+        res, _ = api.compare(tbl, live, gold)
+        want = ref[lo:lo + 4096]
+        finite = np.isfinite(want)
+        got = res["max_abs_err"]
+        assert (got[finite].view(np.uint64) == want[finite].view(np.uint64)).all(), lo
+        assert np.isinf(got[~finite]).all(), lo
+        assert (res["mismatch_count"] == (chunk != 0)).all(), lo
 
 
 def check_compare_worked_example(api):
@@ -710,7 +737,7 @@ def check_timing_stats(api):
 ALL_CHECKS = [
     check_checksum_constants, check_checksum_golden, check_checksum_bruteforce,
     check_checksum_properties, check_checksum_table, check_compare_bruteforce,
-    check_compare_worked_example, check_compare_isclose, check_compare_closed_forms,
+    check_f16_every_pattern, check_compare_worked_example, check_compare_isclose, check_compare_closed_forms,
     check_compare_unfused, check_summary, check_restore, check_dirty_diff, check_table_rules,
     check_eval_loop, check_record, check_writeset_regions, check_eval_guard,
     check_instances, check_timing_stats,

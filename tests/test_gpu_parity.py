@@ -428,6 +428,10 @@ def test_compare_near_tied_relative_errors(env, oracle):
     gb = ri.f32_to_bf16_bits(rng.standard_normal(n) * np.exp2(rng.integers(-60, 60, n))).astype(np.uint16)
     cb = (gb.astype(np.int32) + rng.integers(-2, 3, n)).astype(np.uint16)
     parts.append((ri.BF16, gb.view(np.uint8), cb.view(np.uint8)))
+    gh = (rng.uniform(1, 2, n) * rng.choice([-1.0, 1.0], n) * np.exp2(rng.integers(-12, 12, n)))
+    gh = gh.astype("<f2").view(np.uint16)        # finite, well away from the largest binary16
+    ch = (gh.astype(np.int32) + rng.integers(-2, 3, n)).astype(np.uint16)
+    parts.append((ri.F16, gh.view(np.uint8), ch.view(np.uint8)))
     gi = rng.integers(-(1 << 31), 1 << 31, n).astype("<i4")
     ci = (gi.astype(np.int64) + rng.integers(-3, 4, n)).clip(-(1 << 31), (1 << 31) - 1).astype("<i4")
     parts.append((ri.I32, gi.view(np.uint8), ci.view(np.uint8)))
@@ -462,10 +466,10 @@ def test_twenty_thousand_tiny_regions(env, oracle):
     r3, ctx, torch = env
     rng = np.random.default_rng(2024)
     n = 20000
-    dts = [ri.U8, ri.F32, ri.F64, ri.I32, ri.BF16]
+    dts = [ri.U8, ri.F32, ri.F64, ri.I32, ri.BF16, ri.F16]
     rows, at = [], 0
     for i in range(n):
-        dt = dts[int(rng.integers(0, 5))]
+        dt = dts[int(rng.integers(0, 6))]
         es = ri.ELEM_SIZE[dt]
         nb = int(rng.integers(0, 64 // es + 1)) * es
         at = (at + es - 1) // es * es + int(rng.integers(0, 3)) * es
@@ -526,3 +530,36 @@ def test_restore_few_regions_with_empty_and_tiny_ones(env, oracle):
             got = host(d_live)
             assert (got == exp).all(), (unit, rows[:3], np.flatnonzero(got != exp)[:8])
     assert r3.lib().r3_tune_copy(0, 0) == r3.OK
+
+
+def test_compare_every_binary16_pattern(env, oracle):
+    """R3_F16: all 65536 patterns against all-zero, against themselves shifted by one, and pattern
+    pairs (p, q) on a grid, under both modes: the device's conversion must agree with the oracle's
+    for every value, subnormals, infinities and NaNs included."""
+    r3, ctx, torch = env
+    pats = np.arange(65536, dtype=np.uint16)
+    rng = np.random.default_rng(16)
+    cases = [(pats, np.zeros_like(pats)), (pats, np.roll(pats, 1)), (np.roll(pats, 7), pats),
+             (rng.permutation(pats), rng.permutation(pats)), (np.full_like(pats, 0x3C00), pats)]
+    n = pats.size * 2
+    rows, at = [], 0
+    for i in range(len(cases)):
+        for mode, rtol, atol in ((ri.BITWISE, 0, 0), (ri.TOL, 1e-2, 1e-3), (ri.TOL, 0.0, 0.0)):
+            rows.append((at, n, ri.F16, mode, rtol, atol))
+            at += n
+    live, gold = np.zeros(at, np.uint8), np.zeros(at, np.uint8)
+    for r, (off, nb, *_), in enumerate(rows):
+        c, g = cases[r // 3]
+        live[off:off + nb] = c.view(np.uint8)
+        gold[off:off + nb] = g.view(np.uint8)
+    exp_res, exp_sum = oracle.compare(oracle.make_table(rows), live, gold)
+    res, summ = run_compare(r3, ctx, torch, rows, dev(torch, live), dev(torch, gold), at)
+    assert_results_equal(res, exp_res, "binary16 patterns")
+    assert_results_equal(summ, exp_sum, "summary")
+    # one element per region for a sample of pairs: no maximum can hide a wrong conversion
+    m = 4000
+    p, q = rng.integers(0, 65536, m).astype(np.uint16), rng.integers(0, 65536, m).astype(np.uint16)
+    rows1 = [(2 * i, 2, ri.F16, ri.TOL, 1e-3, 1e-4) for i in range(m)]
+    exp_res, _ = oracle.compare(oracle.make_table(rows1), p.view(np.uint8), q.view(np.uint8))
+    res, _ = run_compare(r3, ctx, torch, rows1, dev(torch, p.view(np.uint8)), dev(torch, q.view(np.uint8)), 2 * m)
+    assert_results_equal(res, exp_res, "single binary16 elements")

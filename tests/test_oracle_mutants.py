@@ -35,6 +35,10 @@ MUTANTS = [
     ("max_only_over_mismatches", "if (d > max_abs) max_abs = d;", "if (mismatch && d > max_abs) max_abs = d;"),
     ("rel_max_only_over_mismatches", "if (r > max_rel) max_rel = r;", "if (mismatch && r > max_rel) max_rel = r;"),
     ("bf16_low_half", "f32_from_bits((uint32_t)h << 16)", "f32_from_bits((uint32_t)h)"),
+    ("f16_exponent_bias", "ldexp((double)(1024 + m), e - 25)", "ldexp((double)(1024 + m), e - 24)"),
+    ("f16_subnormal_scale", "ldexp((double)m, -24)", "ldexp((double)m, -25)"),
+    ("f16_hidden_bit_dropped", "ldexp((double)(1024 + m), e - 25)", "ldexp((double)m, e - 25)"),
+    ("f16_nonfinite_not_flagged", "*val = m ? NAN : INFINITY;\n        *nonfinite = 1;", "*val = m ? NAN : INFINITY;"),
     ("checksum_of_golden", "out->checksum = r3o_checksum_bytes(c_base, rg->bytes);",
      "out->checksum = r3o_checksum_bytes(g_base, rg->bytes);"),
     ("dirty_bit_order", "bitmap[p / 64] |= 1ull << (p % 64);", "bitmap[p / 64] |= 1ull << (63 - p % 64);"),
