@@ -32,9 +32,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # each scaled by what the same counter reads for a plain 1 GiB copy (FETCH 2.0, WRITE 1.0).
 # Valid only for the kernel source they were taken with: reported as null otherwise.
 COUNTERS = {
-    "kernels_sha256_16": "c42d24e1274cac2b",
-    "jacobi": {"restore": 541102311, "validate": 269491067},
-    "large_snapshot": {"restore": 68755014062, "validate": 68734155091},
+    "kernels_sha256_16": "13fb7fe4b7fb8c37",
+    "jacobi": {"restore": 541103237, "validate": 269491186},
+    "large_snapshot": {"restore": 68754964189, "validate": 68734171813},
 }
 
 
