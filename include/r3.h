@@ -54,7 +54,8 @@ typedef enum {
   R3_EOVERLAP = -4,   /* two non-empty regions share a byte                                */
   R3_ENOSPC = -5,     /* workspace too small / too many replays for the workspace          */
   R3_EHIP = -6,       /* a HIP runtime call failed                                         */
-  R3_ECANDIDATE = -7  /* the candidate's launch callback or its kernel launch failed       */
+  R3_ECANDIDATE = -7, /* the candidate's launch callback or its kernel launch failed       */
+  R3_EBUSY = -8       /* r3_eval_try_wait: the evaluation has not finished in the time given */
 } r3_status;
 
 /* Element types of a region: 1, 4, 8, 4, 2, 2 bytes (R3_F16 = IEEE binary16). */
@@ -324,6 +325,15 @@ int r3_eval_submit(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prolo
                    void* stream);
 int r3_eval_wait(r3_ctx* ctx, uint32_t ticket, r3_eval_result* host_out,
                  r3_guard_result* host_guard_out);
+
+/* r3_eval_wait that gives up: looks for the evaluation's end for at most timeout_us
+ * microseconds (0 = look once).  Finished: behaves exactly like r3_eval_wait.  Not finished:
+ * R3_EBUSY, nothing is written, the ticket stays outstanding and can be waited for again.
+ * This is how a caller notices a candidate that runs far longer than anything it could
+ * accept (Section V-C rejects candidates that do not behave); what to do with a kernel that
+ * never ends is the caller's decision, the library cannot stop it. */
+int r3_eval_try_wait(r3_ctx* ctx, uint32_t ticket, uint32_t timeout_us, r3_eval_result* host_out,
+                     r3_guard_result* host_guard_out);
 
 /* ---- write-set driven replay ------------------------------------------- */
 

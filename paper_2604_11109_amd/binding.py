@@ -12,7 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libr3.so")
 
 # status codes
-OK, EINVAL, EALIGN, ERANGE, EOVERLAP, ENOSPC, EHIP, ECANDIDATE = 0, -1, -2, -3, -4, -5, -6, -7
+OK, EINVAL, EALIGN, ERANGE, EOVERLAP, ENOSPC, EHIP, ECANDIDATE, EBUSY = 0, -1, -2, -3, -4, -5, -6, -7, -8
 # element types, modes, policies
 U8, F32, F64, I32, BF16, F16 = 0, 1, 2, 3, 4, 5
 BITWISE, TOL = 0, 1
@@ -72,7 +72,7 @@ DECLARED = [
     "r3_table_validate", "r3_table_workspace_bytes", "r3_table_workspace_bytes_exact",
     "r3_tune_tiles", "r3_tune_copy", "r3_table_create", "r3_table_destroy", "r3_table_info", "r3_restore",
     "r3_checksum", "r3_compare", "r3_dirty_diff", "r3_record", "r3_eval_candidate",
-    "r3_eval_submit", "r3_eval_wait", "r3_eval_submit_guarded",
+    "r3_eval_submit", "r3_eval_wait", "r3_eval_try_wait", "r3_eval_submit_guarded",
     "r3_writeset_regions", "r3_eval_candidate_guarded", "r3_table_replicate",
     "r3_eval_candidate_instances", "r3_ctx_last_times", "r3_timing_stats",
     "r3_replay_workspace_bytes", "r3_replay_create", "r3_replay_run", "r3_replay_destroy",
@@ -127,6 +127,7 @@ def lib():
         L.r3_eval_submit.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, u32, vp,
                                      ctypes.POINTER(u32), vp]
         L.r3_eval_wait.argtypes = [vp, u32, ctypes.POINTER(EvalResult), ctypes.POINTER(GuardResult)]
+        L.r3_eval_try_wait.argtypes = [vp, u32, u32, ctypes.POINTER(EvalResult), ctypes.POINTER(GuardResult)]
         L.r3_eval_submit_guarded.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, u32, vp,
                                              ctypes.POINTER(Guard), ctypes.POINTER(u32), vp]
         L.r3_writeset_regions.argtypes = [vp, u64, u32, ci, vp, u32, ctypes.POINTER(u32)]
@@ -447,6 +448,17 @@ def r3_eval_wait(ctx, ticket, raise_on_candidate=False, with_guard=False):
     if not (rc == ECANDIDATE and not raise_on_candidate):
         ctx.check(rc, "r3_eval_wait")
     return (rc, out, gout) if with_guard else (rc, out)
+
+
+def r3_eval_try_wait(ctx, ticket, timeout_us=0):
+    """Returns None while the evaluation is still running, else (status, EvalResult, GuardResult)."""
+    out, gout = EvalResult(), GuardResult()
+    rc = lib().r3_eval_try_wait(ctx.handle, ticket, timeout_us, ctypes.byref(out), ctypes.byref(gout))
+    if rc == EBUSY:
+        return None
+    if rc != ECANDIDATE:
+        ctx.check(rc, "r3_eval_try_wait")
+    return rc, out, gout
 
 
 def r3_writeset_regions(host_bitmap, nbytes, page_bytes, want_dirty):

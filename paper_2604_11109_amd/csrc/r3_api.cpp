@@ -1,6 +1,7 @@
 // Entry points of libr3.so: argument checks, table upload, and the replay / record loops
 // that string the kernels together on the caller's stream.
 #include <algorithm>
+#include <chrono>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -95,6 +96,7 @@ const char* r3_strerror(int status) {
     case R3_ENOSPC: return "workspace too small";
     case R3_EHIP: return "HIP runtime error";
     case R3_ECANDIDATE: return "candidate failed to launch";
+    case R3_EBUSY: return "not finished yet";
     default: return "unknown status";
   }
 }
@@ -610,6 +612,30 @@ int r3_eval_wait(r3_ctx* ctx, uint32_t ticket, r3_eval_result* host_out, r3_guar
   if (ticket == 0 || ticket > R3_MAX_INFLIGHT || !ctx->lanes[ticket].busy)
     return fail(ctx, R3_EINVAL, "no evaluation in flight under this ticket");
   return eval_collect(ctx, ctx->lanes[ticket], host_out, host_guard_out);
+}
+
+int r3_eval_try_wait(r3_ctx* ctx, uint32_t ticket, uint32_t timeout_us, r3_eval_result* host_out,
+                     r3_guard_result* host_guard_out) {
+  if (ctx == nullptr) return R3_EINVAL;
+  ctx->err.clear();
+  if (host_out == nullptr) return fail(ctx, R3_EINVAL, "pointer is NULL");
+  if (ticket == 0 || ticket > R3_MAX_INFLIGHT || !ctx->lanes[ticket].busy)
+    return fail(ctx, R3_EINVAL, "no evaluation in flight under this ticket");
+  r3::EvalLane& lane = ctx->lanes[ticket];
+  DeviceGuard device_guard(ctx->device);
+  const auto deadline = std::chrono::steady_clock::now() + std::chrono::microseconds(timeout_us);
+  for (;;) {
+    bool done;
+    if (lane.last_flag != nullptr)
+      done = __atomic_load_n(lane.last_flag, __ATOMIC_ACQUIRE) == lane.last_want;
+    else if (lane.end_recorded)
+      done = hipEventQuery(lane.end_event) != hipErrorNotReady;
+    else
+      done = hipStreamQuery(lane.stream) != hipErrorNotReady;
+    if (done) return eval_collect(ctx, lane, host_out, host_guard_out);
+    if (std::chrono::steady_clock::now() >= deadline) break;
+  }
+  return fail(ctx, R3_EBUSY, "the evaluation has not finished yet");
 }
 
 int r3_eval_candidate(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,

@@ -313,3 +313,51 @@ def test_side_stream(env, oracle):
     exp_res, exp_sum = oracle.compare(oracle.make_table(c["check_rows"]), pro, epi)
     assert_results_equal(r3.results_to_numpy(d_regions, nreg), exp_res, "restored state against the epilogue")
     assert_results_equal(r3.summary_to_numpy(d_sum), exp_sum, "summary")
+
+
+def test_try_wait_gives_up_and_can_be_repeated(env, oracle):
+    """r3_eval_try_wait on an evaluation that takes tens of milliseconds: a zero timeout reports that it
+    is still running and leaves the ticket alone; later calls get the verdict that r3_eval_wait gives."""
+    r3, wl, ctx, torch = env
+    c = ri.jacobi(256)
+    A = c["arena_bytes"]
+    tbl = r3.Table(ctx, c["restore_rows"], A)
+    chk = r3.Table(ctx, c["check_rows"], A)
+    d_live = dev(torch, c["prologue"])
+    d_pro = torch.empty(A, dtype=torch.uint8, device="cuda:0")
+    d_epi = torch.empty(A, dtype=torch.uint8, device="cuda:0")
+    r3.r3_record(ctx, tbl, d_live, wl.jacobi_launch(), wl.jacobi_args(c, 64, 1, 0), d_pro, d_epi, 4096,
+                 None, None, None, None)
+    nreg = len(c["check_rows"])
+    bufs = [torch.zeros(40 * nreg, dtype=torch.uint8, device="cuda:0") for _ in range(2)]
+    bug = wl.jacobi_args(c, 128, 2, 1)
+    rc, ref = r3.r3_eval_candidate(ctx, tbl, d_pro, chk, d_epi, d_live, wl.jacobi_launch(), bug, 0, 1,
+                                   r3.EVERY, bufs[0])
+    exp_res, _ = oracle.compare(oracle.make_table(c["check_rows"]), host(d_live), host(d_epi))
+    assert_results_equal(r3.results_to_numpy(bufs[0], nreg), exp_res, "one replay")
+    torch.cuda.synchronize()
+    # 300 replays of ~0.2 ms each: far from finished when the submission returns
+    t = r3.r3_eval_submit(ctx, tbl, d_pro, chk, d_epi, d_live, wl.jacobi_launch(), bug, 0, 300, r3.EVERY, bufs[1])
+    assert r3.r3_eval_try_wait(ctx, t, 0) is None
+    assert r3.r3_eval_try_wait(ctx, t, 200) is None          # 0.2 ms more: still running
+    got = None
+    for _ in range(2000):                                     # at most 2000 x 10 ms
+        got = r3.r3_eval_try_wait(ctx, t, 10000)
+        if got is not None:
+            break
+    assert got is not None
+    rc, out, g = got
+    assert rc == r3.OK and out.passed == 0
+    for f in ("total_mismatch", "first_region", "first_index", "max_abs_err", "max_rel_err"):
+        assert getattr(out, f) == getattr(ref, f), f
+    assert_results_equal(r3.results_to_numpy(bufs[1], nreg), exp_res, "300 replays")
+    assert len(ctx.last_times()) == 300
+    # the ticket is spent now
+    with pytest.raises(r3.R3Error) as e:
+        r3.r3_eval_try_wait(ctx, t, 0)
+    assert e.value.status == r3.EINVAL
+    # a submission that validates only the first replay ends in an event, not in a posted number
+    t = r3.r3_eval_submit(ctx, tbl, d_pro, chk, d_epi, d_live, wl.jacobi_launch(), bug, 0, 100, r3.FIRST, bufs[1])
+    assert r3.r3_eval_try_wait(ctx, t, 0) is None
+    rc, out = r3.r3_eval_wait(ctx, t)
+    assert rc == r3.OK and out.total_mismatch == ref.total_mismatch
