@@ -33,8 +33,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # Valid only for the kernel source they were taken with: reported as null otherwise.
 COUNTERS = {
     "kernels_sha256_16": "13fb7fe4b7fb8c37",
-    "jacobi": {"restore": 541103237, "validate": 269491186},
-    "large_snapshot": {"restore": 68754964189, "validate": 68734171813},
+    "jacobi": {"restore": 541102618, "validate": 269371953},
+    "large_snapshot": {"restore": 68754396689, "validate": 68734331249},
 }
 
 
@@ -61,6 +61,7 @@ def parse():
                    help="evaluations kept in flight (r3_eval_submit / r3_eval_wait); 1 = the synchronous "
                         "r3_eval_candidate")
     p.add_argument("--no-large", action="store_true", help="skip the extra large-snapshot leg")
+    p.add_argument("--no-others", action="store_true", help="skip the short legs of the other workloads")
     p.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run 5 plain copies of 1 GiB (plain_copy_kernel), the yardstick for "
@@ -479,6 +480,28 @@ def large_leg(r3, wl, ctx, torch):
     return out
 
 
+def other_legs(r3, wl, ctx, torch, skip, inflight, defaults):
+    """Evaluations/s and stage rates of the workloads that are neither the headline one nor the
+    large snapshot, so that one run records all five."""
+    out = {}
+    for name in ("replay_small", "many_regions", "spmv"):
+        if name == skip:
+            continue
+        rp = Replay(name, r3, wl, ctx, torch)
+        steps, warmup = defaults[name]
+        steps = max(64, steps // 2)
+        dt, prof = timed_run(rp, steps, warmup, inflight)
+        st = stage_report(rp, prof)
+        leg = {"workload": rp.desc, "value": steps / dt, "unit": "evals/s", "steps": steps,
+               "ms_per_step": dt / steps * 1e3, "evaluations_in_flight": inflight, "stages": st}
+        if name == "spmv":
+            leg["write_set_replay"] = writeset_leg(rp, steps, warmup, inflight)
+        out[name] = leg
+        del rp
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -536,6 +559,8 @@ def main():
         line["write_set_replay"] = writeset_leg(rp, steps, warmup, a.inflight)
     del rp
     torch.cuda.empty_cache()
+    if not a.no_others:
+        line["other_workloads"] = other_legs(r3, wl, ctx, torch, a.workload, a.inflight, defaults)
     if a.workload != "large_snapshot" and not a.no_large:
         line["large_snapshot"] = large_leg(r3, wl, ctx, torch)
     print(json.dumps(line))
