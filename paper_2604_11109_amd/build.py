@@ -17,6 +17,8 @@ COMMON = [
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 
+HOST_NOTE = "'-packed-fp32-ops' is not a recognized feature for this target (ignoring feature)"
+
 LIBS = {
     "libr3.so": ["r3_table.cpp", "r3_api.cpp", "r3_kernels.hip"],
     "libr3_workloads.so": ["workloads/r3w_workloads.hip"],
@@ -37,7 +39,15 @@ def build_lib(name, verbose=True):
     cmd = [HIPCC] + COMMON + ["-x", "hip"] + srcs + ["-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    # The packed-fp32 switch is a device feature; clang's driver refuses to forward -Xclang to
+    # one side only, so the host passes see it too and answer with HOST_NOTE.  That one known
+    # line is dropped, everything else the compiler says is shown.
+    shown = [l for l in res.stdout.splitlines() if l.strip() != HOST_NOTE]
+    if shown:
+        print("\n".join(shown), flush=True)
+    if res.returncode != 0:
+        raise subprocess.CalledProcessError(res.returncode, cmd)
     os.replace(tmp, out)
     return out
 

@@ -105,3 +105,56 @@ def test_jacobi_three_instances(env, oracle):
         r3.r3_eval_candidate_instances(ctx, tbl, d_pro, tbl, d_epi, d_live, None, None, k, stride * 4, 0, 1,
                                        r3.EVERY, d_regions)
     assert e.value.status == r3.ERANGE
+
+
+@pytest.mark.timeout(600)
+def test_jacobi_two_instances_full_size(env, oracle):
+    """Two recorded instances of the 256^3 Jacobi state in one super arena: regions of 128 MiB (16 KiB
+    tiles) next to a 12 KiB side region per instance (4 KiB tiles), so the restore launch mixes size
+    classes and the validation folds thousands of partials per region."""
+    r3, wl, ctx, torch = env
+    n, k = 256, 2
+    cases = [ri.jacobi(n, seed=1002 + 10 * i) for i in range(k)]
+    c0 = cases[0]
+    A = c0["arena_bytes"]
+    side = 3 * 4096
+    stride = A + side + 4096                            # side region, then a gap
+    total = (k - 1) * stride + A + side
+    rng = np.random.default_rng(4242)
+    pro = np.zeros(total, dtype=np.uint8)
+    for i, c in enumerate(cases):
+        pro[i * stride:i * stride + A] = c["prologue"]
+        pro[i * stride + A:i * stride + A + side] = rng.integers(0, 256, size=side, dtype=np.uint8)
+    one = list(c0["restore_rows"]) + [(A, side, ri.I32, ri.BITWISE, 0.0, 0.0)]
+    rows = r3.r3_table_replicate(r3.make_table(one), stride, k)
+    assert rows.tobytes() == oracle.replicate_table(oracle.make_table(one), stride, k).tobytes()
+    tbl = r3.Table(ctx, rows, total)
+    d_pro = dev(torch, pro)
+    d_epi = d_pro.clone()
+    d_live = torch.full((total,), 0x33, dtype=torch.uint8, device="cuda:0")
+    base = wl.jacobi_args(c0, 64, 1, 0)
+    launch = wl.lib().r3w_jacobi_launch
+    launch.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    for i in range(k):
+        assert launch(ctypes.addressof(base), d_epi.data_ptr() + i * stride, 0) == 0
+    torch.cuda.synchronize()
+    epi = host(d_epi)
+    d_regions = torch.zeros(40 * tbl.n, dtype=torch.uint8, device="cuda:0")
+    for block, unroll, bug in [(512, 1, 0), (128, 2, 1)]:
+        print("case instances 256^3 x 2", block, unroll, bug, flush=True)
+        args = wl.jacobi_args(c0, block, unroll, bug)
+        rc, out, flags = r3.r3_eval_candidate_instances(ctx, tbl, d_pro, tbl, d_epi, d_live, wl.jacobi_launch(),
+                                                        args, k, stride, 0, 1, r3.EVERY, d_regions)
+        live = host(d_live)
+        exp_res, exp_sum = oracle.compare(oracle.make_table(rows), live, epi)
+        s = exp_sum[0]
+        assert rc == r3.OK
+        assert r3.results_to_numpy(d_regions, tbl.n).tobytes() == exp_res.tobytes()
+        assert out.total_mismatch == int(s["total_mismatch"]) == (k * (n - 2) ** 2 if bug else 0)
+        assert out.first_region == int(s["first_region"]) and out.first_index == int(s["first_index"])
+        assert np.float64(out.max_abs_err).tobytes() == s["max_abs_err"].tobytes()
+        assert np.float64(out.max_rel_err).tobytes() == s["max_rel_err"].tobytes()
+        assert list(flags) == [int(not bug)] * k and out.passed == int(not bug)
+        if bug:
+            assert out.first_region == 1 and out.first_index == (1 * n + 1) * n + (n - 2)
+        assert (live[A + side:stride] == 0x33).all()    # the gap between the instances is untouched

@@ -344,6 +344,8 @@ def test_region_larger_than_4_gib(env, oracle):
         hi = min(n + 11, lo + (1 << 30))
         d_gold[lo:hi] = torch.randint(0, 256, (hi - lo,), generator=gen, device="cuda:0", dtype=torch.uint8)
     d_live = torch.empty_like(d_gold)
+    d_live[n - 64:n] = 0x5A
+    d_live[n:] = 0xA5                                  # canary past the ragged tail
     rows = [(0, n, ri.U8, ri.BITWISE, 0, 0)]
     tbl = r3.Table(ctx, rows, n)
     r3.r3_restore(ctx, tbl, d_gold, d_live)
@@ -361,8 +363,11 @@ def test_region_larger_than_4_gib(env, oracle):
     assert int(res["mismatch_count"]) == 3 and int(res["first_mismatch"]) == planted[0]
     assert float(res["max_abs_err"]) == 16.0
     assert int(summ["total_mismatch"]) == 3 and int(summ["first_index"]) == planted[0]
-    # the bytes past the region were not copied
-    assert (host(d_live[n:]) != host(d_gold[n:])).any() or True
+    # the bytes past the region were not written, the last bytes of the region were
+    assert (host(d_live[n:]) == 0xA5).all()
+    tail_live, tail_gold = host(d_live[n - 64:n]), host(d_gold[n - 64:n])
+    tail_gold[-1] ^= 0x10                              # the planted change at n - 1
+    assert (tail_live == tail_gold).all()
     # checksum of the 5 GiB of live bytes against the oracle (fused and stand-alone kernels)
     live_h = host(d_live[:n])
     exp = oracle.checksum(oracle.make_table(rows), live_h)
