@@ -420,6 +420,32 @@ int r3_replay_run(r3_replay* rp, uint32_t warmup, uint32_t reps, r3_eval_result*
                   void* stream);
 int r3_replay_destroy(r3_replay* rp);
 
+/* ---- validation for callers that cannot allocate ------------------------- */
+
+/* r3_compare for callers that may not allocate device memory and hold no table object: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The caller
+ * passes the regions themselves (host memory, read during the call, not retained) instead of a
+ * table; they travel to the kernels as launch arguments, and the per-tile partial results go to
+ * a buffer that is part of the library's device image (R3_STATIC_MAX_TILES x 40 bytes = 640 KiB
+ * on every GPU the library has a context on, held until the process ends) instead of a
+ * caller-provided workspace.  The call enqueues two or three kernels on `stream` and returns;
+ * it calls no allocating routine, performs no copy and does not wait.
+ * Results: d_out (device, n results) and d_summary (device, may be NULL) exactly as r3_compare
+ * on a table made from the same regions.
+ * Limits: n <= R3_STATIC_MAX_REGIONS, and the regions must split into at most
+ * R3_STATIC_MAX_TILES tiles of at most R3_STATIC_MAX_TILE_BYTES bytes each (the tile size is the
+ * smallest power of two >= 4 KiB for which the tile count fits): R3_ENOSPC beyond, with
+ * r3_last_error saying which limit.  Table rules and their status codes as r3_table_validate.
+ * Every call on one GPU uses that GPU's one buffer, and the buffer keeps the previous call's
+ * partials until they are overwritten: calls on the same GPU must not overlap in time (same
+ * stream, or ordered by events); overlapping calls race. */
+#define R3_STATIC_MAX_REGIONS 16u
+#define R3_STATIC_MAX_TILES 16384u
+#define R3_STATIC_MAX_TILE_BYTES (16u << 20)
+int r3_compare_static(r3_ctx* ctx, const r3_region* host_tbl, uint32_t n, uint64_t arena_bytes,
+                      const void* d_live, const void* d_golden, r3_region_result* d_out,
+                      r3_summary* d_summary, void* stream);
+
 /* ---- timing statistics -------------------------------------------------- */
 
 /* Candidate times (ms) of the timed replays of the last evaluation on ctx, in replay order:

@@ -76,6 +76,7 @@ DECLARED = [
     "r3_writeset_regions", "r3_eval_candidate_guarded", "r3_table_replicate",
     "r3_eval_candidate_instances", "r3_ctx_last_times", "r3_timing_stats",
     "r3_replay_workspace_bytes", "r3_replay_create", "r3_replay_run", "r3_replay_destroy",
+    "r3_compare_static",
 ]
 
 _lib = None
@@ -120,6 +121,7 @@ def lib():
         L.r3_restore.argtypes = [vp, vp, vp, vp, vp]
         L.r3_checksum.argtypes = [vp, vp, vp, vp, vp]
         L.r3_compare.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        L.r3_compare_static.argtypes = [vp, vp, u32, u64, vp, vp, vp, vp, vp]
         L.r3_dirty_diff.argtypes = [vp, vp, vp, u64, u32, vp, vp, vp]
         L.r3_record.argtypes = [vp, vp, vp, vp, vp, vp, vp, u32, vp, vp, vp, vp, vp]
         L.r3_eval_candidate.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, u32, vp,
@@ -334,6 +336,21 @@ def r3_compare(ctx, tbl, d_live, d_golden, d_out, d_summary=None, stream=None):
     _need(d_summary, 40, "summary")
     ctx.check(lib().r3_compare(ctx.handle, tbl.handle, _ptr(d_live), _ptr(d_golden), _ptr(d_out),
                                _ptr(d_summary), _stream(stream)), "r3_compare")
+
+
+STATIC_MAX_REGIONS, STATIC_MAX_TILES, STATIC_MAX_TILE_BYTES = 16, 16384, 16 << 20
+
+
+def r3_compare_static(ctx, rows, arena_bytes, d_live, d_golden, d_out, d_summary=None, stream=None):
+    """r3_compare without a table object: the regions go in as host rows."""
+    t = _host_table(rows if isinstance(rows, np.ndarray) else make_table(rows))
+    _need(d_live, arena_bytes, "live arena")
+    _need(d_golden, arena_bytes, "golden arena")
+    _need(d_out, 40 * len(t), "region results")
+    _need(d_summary, 40, "summary")
+    ctx.check(lib().r3_compare_static(ctx.handle, t.ctypes.data if len(t) else None, len(t), int(arena_bytes),
+                                      _ptr(d_live), _ptr(d_golden), _ptr(d_out), _ptr(d_summary),
+                                      _stream(stream)), "r3_compare_static")
 
 
 def bitmap_words(nbytes, page_bytes):

@@ -114,6 +114,9 @@ int r3_ctx_create(r3_ctx** out, int device) {
     delete ctx;
     return R3_EHIP;
   }
+  // Where this device keeps the library's own partials buffer (used by r3_compare_static only;
+  // a failure here is reported by that call).
+  ctx->static_scratch_status = r3::static_scratch_address(device, &ctx->static_scratch);
   *out = ctx;
   return R3_OK;
 }
@@ -263,6 +266,61 @@ int r3_compare(r3_ctx* ctx, const r3_table* tbl, const void* d_live, const void*
   hipError_t e = r3::launch_compare(tbl->dev, d_live, d_golden, d_out, d_summary, nullptr, 0, nullptr,
                                     as_stream(stream));
   return e == hipSuccess ? R3_OK : fail_hip(ctx, e, "compare launch");
+}
+
+int r3_compare_static(r3_ctx* ctx, const r3_region* host_tbl, uint32_t n, uint64_t arena_bytes,
+                      const void* d_live, const void* d_golden, r3_region_result* d_out,
+                      r3_summary* d_summary, void* stream) {
+  if (ctx == nullptr) return R3_EINVAL;
+  ctx->err.clear();
+  if (host_tbl == nullptr || n == 0) return fail(ctx, R3_EINVAL, "region table is empty");
+  if (n > R3_STATIC_MAX_REGIONS) return fail(ctx, R3_ENOSPC, "more than R3_STATIC_MAX_REGIONS regions");
+  // The rules of r3_table_validate, written without host allocations (n is small).
+  for (uint32_t i = 0; i < n; ++i) {
+    const r3_region& r = host_tbl[i];
+    const uint32_t es = r3::elem_size(r.dtype);
+    if (es == 0 || (r.mode != R3_CMP_BITWISE && r.mode != R3_CMP_TOL) || !(r.rtol >= 0) || !(r.atol >= 0) ||
+        r.rtol > 1.7976931348623157e308 || r.atol > 1.7976931348623157e308)
+      return fail(ctx, R3_EINVAL, "region table rejected");
+    if ((r.offset % es) || (r.bytes % es)) return fail(ctx, R3_EALIGN, "region table rejected");
+    if (r.offset > arena_bytes || r.bytes > arena_bytes - r.offset)
+      return fail(ctx, R3_ERANGE, "region table rejected");
+  }
+  for (uint32_t i = 0; i < n; ++i)
+    for (uint32_t j = i + 1; j < n; ++j) {
+      const r3_region &a = host_tbl[i], &b = host_tbl[j];
+      if (a.bytes && b.bytes && a.offset < b.offset + b.bytes && b.offset < a.offset + a.bytes)
+        return fail(ctx, R3_EOVERLAP, "region table rejected");
+    }
+  if (d_live == nullptr || d_golden == nullptr || d_out == nullptr)
+    return fail(ctx, R3_EINVAL, "pointer is NULL");
+  if (!aligned16(d_live) || !aligned16(d_golden)) return fail(ctx, R3_EALIGN, "arena base not 16-byte aligned");
+  if (ctx->static_scratch == nullptr)
+    return fail_hip(ctx, ctx->static_scratch_status != hipSuccess ? ctx->static_scratch_status : hipErrorInvalidSymbol,
+                    "the library's partials buffer could not be resolved on this device");
+  // One tile size for all regions: the smallest that keeps the tile count within the buffer.
+  r3::StaticTable st{};
+  st.n = n;
+  uint32_t shift = 12;
+  for (;; ++shift) {
+    if ((1ull << shift) > R3_STATIC_MAX_TILE_BYTES)
+      return fail(ctx, R3_ENOSPC, "regions need more than R3_STATIC_MAX_TILES tiles of R3_STATIC_MAX_TILE_BYTES");
+    uint64_t tiles = 0;
+    for (uint32_t i = 0; i < n; ++i) tiles += (host_tbl[i].bytes + ((1ull << shift) - 1)) >> shift;
+    if (tiles <= R3_STATIC_MAX_TILES) break;
+  }
+  st.shift = shift;
+  uint32_t at = 0;
+  for (uint32_t i = 0; i < n; ++i) {
+    st.regions[i] = host_tbl[i];
+    st.tile_begin[i] = at;
+    at += (uint32_t)((host_tbl[i].bytes + ((1ull << shift) - 1)) >> shift);
+  }
+  for (uint32_t i = n; i <= R3_STATIC_MAX_REGIONS; ++i) st.tile_begin[i] = at;
+  DeviceGuard guard(ctx->device);
+  hipError_t e = r3::launch_compare_static(st, d_live, d_golden, ctx->static_scratch, d_out, d_summary,
+                                           as_stream(stream));
+  return e == hipSuccess ? R3_OK : fail_hip(ctx, e, "static compare launch");
 }
 
 static bool page_ok(uint32_t page_bytes) {

@@ -81,6 +81,15 @@ struct TableDev {
   uint64_t n_tiles;
 };
 
+// A small table that travels in the launch arguments (r3_compare_static): every region is
+// split into tiles of the same size 2^shift; tile_begin is the prefix sum of tiles per region.
+struct StaticTable {
+  r3_region regions[R3_STATIC_MAX_REGIONS];
+  uint32_t tile_begin[R3_STATIC_MAX_REGIONS + 1];
+  uint32_t n;
+  uint32_t shift;
+};
+
 // One slot of the pinned host buffer that the replay loop hands to the finalize pass: the
 // table summary and, written after it with a system-scope release, the sequence number of
 // the validation that produced it (what the host polls for).
@@ -136,6 +145,12 @@ hipError_t launch_checksum(const TableDev& t, const void* arena, uint64_t* out, 
 hipError_t launch_compare(const TableDev& t, const void* live, const void* golden,
                           r3_region_result* out, r3_summary* summary, HostSlot* host_slot,
                           uint64_t host_seq, const uint32_t* rep_counter, hipStream_t s);
+// The library's own partials buffer on the current device (resolved once per device; the
+// device must be current).  launch_compare_static takes that address, never the symbol.
+hipError_t static_scratch_address(int device, Partial** out);
+hipError_t launch_compare_static(const StaticTable& st, const void* live, const void* golden,
+                                 Partial* scratch, r3_region_result* out, r3_summary* summary,
+                                 hipStream_t s);
 hipError_t launch_stamp(uint32_t* rep_counter, uint64_t* stamps, uint32_t which, hipStream_t s);
 hipError_t launch_set_counter(uint32_t* rep_counter, uint32_t value, hipStream_t s);
 hipError_t launch_guard_compare(const uint64_t* got, const uint64_t* expected, uint32_t n,
@@ -185,6 +200,8 @@ struct r3_ctx {
   uint32_t profile_period = 0;         // 0 = off, n = stage events on every n-th evaluation
   uint64_t evals = 0;
   r3_profile profile{};
+  r3::Partial* static_scratch = nullptr;  // this device's copy of the library's partials buffer
+  hipError_t static_scratch_status = hipSuccess;
 };
 
 struct r3_table {

@@ -11,6 +11,8 @@
 //
 // Floating point in the validation follows the rule in r3.h: binary64, one rounding per
 // operation.  This file is compiled with -ffp-contract=off; the pragma below repeats that.
+#include <algorithm>
+
 #include "r3_internal.h"
 
 #pragma clang fp contract(off)
@@ -709,11 +711,9 @@ __device__ __forceinline__ void compare_tile(const uint8_t* cbase, const uint8_t
   }
 }
 
-__global__ __launch_bounds__(kBlock) void compare_kernel(TableDev t, const uint8_t* live,
-                                                         const uint8_t* golden) {
-  const uint64_t tile_id = (uint64_t)blockIdx.x * kWavesPerBlock + wave_in_block();
-  if (tile_id >= t.n_tiles) return;
-  const TileView tv = resolve_tile(t, tile_id);
+// Validate one tile and leave its partial at *dst (all 64 lanes of the wavefront take part).
+__device__ __forceinline__ void compare_tile_to_partial(const TileView& tv, const uint8_t* live,
+                                                        const uint8_t* golden, Partial* dst) {
   const uint64_t at = tv.offset + tv.rel_start;
   const uint64_t word0 = tv.rel_start >> 3;
   const uint32_t lane = lane_id();
@@ -745,12 +745,20 @@ __global__ __launch_bounds__(kBlock) void compare_kernel(TableDev t, const uint8
     max_rel = dpp_max(dbits(a.max_rel));
     if (first != 0xFFFFFFFFu) first_elem = tv.rel_start / k.es + first;
   }
-  uint64_t* out = (uint64_t*)&t.partials[tile_id];
+  uint64_t* out = (uint64_t*)dst;
   if (lane < 5) {
     const uint64_t val = lane == 0 ? count : lane == 1 ? first_elem : lane == 2 ? max_abs
                        : lane == 3 ? max_rel : cks;
     out[lane] = val;
   }
+}
+
+__global__ __launch_bounds__(kBlock) void compare_kernel(TableDev t, const uint8_t* live,
+                                                         const uint8_t* golden) {
+  const uint64_t tile_id = (uint64_t)blockIdx.x * kWavesPerBlock + wave_in_block();
+  if (tile_id >= t.n_tiles) return;
+  const TileView tv = resolve_tile(t, tile_id);
+  compare_tile_to_partial(tv, live, golden, &t.partials[tile_id]);
 }
 
 // One block per region folds that region's partials into its r3_region_result.  The table
@@ -777,71 +785,80 @@ __device__ __forceinline__ void write_summary(r3_summary* dst, uint64_t total, u
   dst->max_rel_err = bits_d(max_rel);
 }
 
+// Fold partials [b, e) with one block; the result is complete in thread 0.
+template <int BLOCK>
+__device__ __forceinline__ Folded fold_partials(const Partial* partials, uint64_t b, uint64_t e,
+                                                uint64_t (*sh)[BLOCK / 64]) {
+  constexpr int NW = BLOCK / 64;
+  constexpr int kAhead = 8;  // partials fetched per thread before any is folded
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  Folded f{0, R3_NO_INDEX, 0, 0, 0};
+  for (uint64_t i = b + tid; i < e; i += (uint64_t)BLOCK * kAhead) {
+    uint64_t v[kAhead][5];
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) {
+      const uint64_t idx = i + (uint64_t)u * BLOCK;
+      if (idx < e) {
+        const uint64_t* p = (const uint64_t*)&partials[idx];
+#pragma unroll
+        for (int k = 0; k < 5; ++k) v[u][k] = p[k];
+      } else {
+        v[u][0] = 0; v[u][1] = R3_NO_INDEX; v[u][2] = 0; v[u][3] = 0; v[u][4] = 0;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) {
+      f.count += v[u][0];
+      f.first = v[u][1] < f.first ? v[u][1] : f.first;
+      f.max_abs = v[u][2] > f.max_abs ? v[u][2] : f.max_abs;
+      f.max_rel = v[u][3] > f.max_rel ? v[u][3] : f.max_rel;
+      f.cks += v[u][4];
+    }
+  }
+  f.count = dpp_sum(f.count);
+  f.first = dpp_min(f.first);
+  f.max_abs = dpp_max(f.max_abs);
+  f.max_rel = dpp_max(f.max_rel);
+  f.cks = dpp_sum(f.cks);
+  if (NW > 1) {
+    if (lane == 0) {
+      sh[0][wave] = f.count; sh[1][wave] = f.first; sh[2][wave] = f.max_abs;
+      sh[3][wave] = f.max_rel; sh[4][wave] = f.cks;
+    }
+    __syncthreads();
+    if (wave == 0) {  // the first wavefront folds the per-wavefront values, again over DPP
+      const bool on = lane < (uint32_t)NW;
+      const uint64_t zero = 0, none = R3_NO_INDEX;
+      f.count = dpp_sum((uint64_t)(on ? sh[0][lane] : zero));
+      f.first = dpp_min((uint64_t)(on ? sh[1][lane] : none));
+      f.max_abs = dpp_max((uint64_t)(on ? sh[2][lane] : zero));
+      f.max_rel = dpp_max((uint64_t)(on ? sh[3][lane] : zero));
+      f.cks = dpp_sum((uint64_t)(on ? sh[4][lane] : zero));
+    }
+  }
+  return f;
+}
+
+__device__ __forceinline__ void write_region_result(r3_region_result* dst, const Folded& f,
+                                                    uint64_t region_bytes) {
+  uint64_t* o = (uint64_t*)dst;
+  o[0] = f.count;
+  o[1] = f.first;
+  o[2] = f.max_abs;
+  o[3] = f.max_rel;
+  o[4] = f.cks + region_bytes * kLen;
+}
+
 template <int BLOCK>
 __global__ __launch_bounds__(BLOCK) void compare_finalize_kernel(TableDev t, r3_region_result* out,
                                                                  r3_summary* summary,
                                                                  HostSlot* host_slot, uint64_t host_seq,
                                                                  const uint32_t* rep_counter) {
-  constexpr int NW = BLOCK / 64;
-  constexpr int kAhead = 8;  // partials fetched per thread before any is folded
-  __shared__ uint64_t sh[5][NW];
+  __shared__ uint64_t sh[5][BLOCK / 64];
   const uint32_t r = blockIdx.x;
-  const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  Folded f{0, R3_NO_INDEX, 0, 0, 0};
-  {
-    const uint64_t b = t.tile_begin[r], e = t.tile_begin[r + 1];
-    for (uint64_t i = b + tid; i < e; i += (uint64_t)BLOCK * kAhead) {
-      uint64_t v[kAhead][5];
-#pragma unroll
-      for (int u = 0; u < kAhead; ++u) {
-        const uint64_t idx = i + (uint64_t)u * BLOCK;
-        if (idx < e) {
-          const uint64_t* p = (const uint64_t*)&t.partials[idx];
-#pragma unroll
-          for (int k = 0; k < 5; ++k) v[u][k] = p[k];
-        } else {
-          v[u][0] = 0; v[u][1] = R3_NO_INDEX; v[u][2] = 0; v[u][3] = 0; v[u][4] = 0;
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < kAhead; ++u) {
-        f.count += v[u][0];
-        f.first = v[u][1] < f.first ? v[u][1] : f.first;
-        f.max_abs = v[u][2] > f.max_abs ? v[u][2] : f.max_abs;
-        f.max_rel = v[u][3] > f.max_rel ? v[u][3] : f.max_rel;
-        f.cks += v[u][4];
-      }
-    }
-    f.count = dpp_sum(f.count);
-    f.first = dpp_min(f.first);
-    f.max_abs = dpp_max(f.max_abs);
-    f.max_rel = dpp_max(f.max_rel);
-    f.cks = dpp_sum(f.cks);
-    if (NW > 1) {
-      if (lane == 0) {
-        sh[0][wave] = f.count; sh[1][wave] = f.first; sh[2][wave] = f.max_abs;
-        sh[3][wave] = f.max_rel; sh[4][wave] = f.cks;
-      }
-      __syncthreads();
-      if (wave == 0) {  // the first wavefront folds the per-wavefront values, again over DPP
-        const bool on = lane < (uint32_t)NW;
-        const uint64_t zero = 0, none = R3_NO_INDEX;
-        f.count = dpp_sum((uint64_t)(on ? sh[0][lane] : zero));
-        f.first = dpp_min((uint64_t)(on ? sh[1][lane] : none));
-        f.max_abs = dpp_max((uint64_t)(on ? sh[2][lane] : zero));
-        f.max_rel = dpp_max((uint64_t)(on ? sh[3][lane] : zero));
-        f.cks = dpp_sum((uint64_t)(on ? sh[4][lane] : zero));
-      }
-    }
-    if (tid == 0) {
-      uint64_t* o = (uint64_t*)&out[r];
-      o[0] = f.count;
-      o[1] = f.first;
-      o[2] = f.max_abs;
-      o[3] = f.max_rel;
-      o[4] = f.cks + t.regions[r].bytes * kLen;
-    }
-  }
+  const uint32_t tid = threadIdx.x;
+  const Folded f = fold_partials<BLOCK>(t.partials, t.tile_begin[r], t.tile_begin[r + 1], sh);
+  if (tid == 0) write_region_result(&out[r], f, t.regions[r].bytes);
   // A table of one region: its result is the summary.  Larger tables get their summary from
   // summary_kernel, a separate launch: folding it in here through a "last block" ticket
   // needs a device-wide release fence per block, which cost 37 ns per region (150 us for
@@ -856,6 +873,49 @@ __global__ __launch_bounds__(BLOCK) void compare_finalize_kernel(TableDev t, r3_
       write_summary(&host_slot[k].summary, f.count, fr, fi, f.max_abs, f.max_rel);
       publish_seq(host_slot + k, host_seq + k);
     }
+  }
+}
+
+// ---- validation without a table object or a caller workspace (r3_compare_static) -------
+// The partials of these launches live in the library's device image.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; kernels get the resolved address.
+static __device__ __align__(256) unsigned char scratch[(size_t)R3_STATIC_MAX_TILES * sizeof(Partial)];
+
+__global__ __launch_bounds__(kBlock) void compare_static_kernel(StaticTable st, const uint8_t* live,
+                                                                const uint8_t* golden, Partial* partials) {
+  const uint32_t tile_id = blockIdx.x * kWavesPerBlock + wave_in_block();
+  if (tile_id >= st.tile_begin[st.n]) return;
+  uint32_t r = 0;  // the region whose tile range holds tile_id (empty regions are skipped)
+  while (r + 1 < st.n && tile_id >= st.tile_begin[r + 1]) ++r;
+  r = sgpr(r);
+  const r3_region& rg = st.regions[r];
+  TileView tv;
+  tv.region = r;
+  tv.offset = rg.offset;
+  tv.bytes = rg.bytes;
+  tv.dtype = rg.dtype;
+  tv.mode = rg.mode;
+  tv.rtol = rg.rtol;
+  tv.atol = rg.atol;
+  tv.rel_start = (uint64_t)(tile_id - st.tile_begin[r]) << st.shift;
+  const uint64_t left = tv.bytes - tv.rel_start, full = 1ull << st.shift;
+  tv.len = (uint32_t)(left < full ? left : full);
+  compare_tile_to_partial(tv, live, golden, &partials[tile_id]);
+}
+
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void compare_static_finalize_kernel(StaticTable st,
+                                                                        const Partial* partials,
+                                                                        r3_region_result* out,
+                                                                        r3_summary* summary) {
+  __shared__ uint64_t sh[5][BLOCK / 64];
+  const uint32_t r = blockIdx.x;
+  const Folded f = fold_partials<BLOCK>(partials, st.tile_begin[r], st.tile_begin[r + 1], sh);
+  if (threadIdx.x == 0) {
+    write_region_result(&out[r], f, st.regions[r].bytes);
+    if (gridDim.x == 1 && summary != nullptr)
+      write_summary(summary, f.count, f.count ? 0u : R3_NO_REGION, f.count ? f.first : R3_NO_INDEX,
+                    f.max_abs, f.max_rel);
   }
 }
 
@@ -1144,6 +1204,50 @@ hipError_t launch_compare(const TableDev& t, const void* live, const void* golde
   hipError_t e = hipGetLastError();
   if (e == hipSuccess && t.n_regions > 1 && (summary != nullptr || host_slot != nullptr)) {
     summary_kernel<<<1, kBlock, 0, s>>>(out, t.n_regions, summary, host_slot, host_seq, rep_counter);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+hipError_t static_scratch_address(int device, Partial** out) {
+  constexpr int kMaxDevices = 64;
+  static Partial* resolved[kMaxDevices] = {};  // each GPU holds its own copy at its own address
+  *out = nullptr;
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  Partial* p = __atomic_load_n(&resolved[device], __ATOMIC_ACQUIRE);
+  if (p == nullptr) {
+    void* addr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (addr == nullptr) return hipErrorInvalidSymbol;
+    p = static_cast<Partial*>(addr);
+    __atomic_store_n(&resolved[device], p, __ATOMIC_RELEASE);
+  }
+  *out = p;
+  return hipSuccess;
+}
+
+hipError_t launch_compare_static(const StaticTable& st, const void* live, const void* golden,
+                                 Partial* scratch_ptr, r3_region_result* out, r3_summary* summary,
+                                 hipStream_t s) {
+  const uint32_t n_tiles = st.tile_begin[st.n];
+  uint32_t max_region_tiles = 0;
+  for (uint32_t r = 0; r < st.n; ++r)
+    max_region_tiles = std::max(max_region_tiles, st.tile_begin[r + 1] - st.tile_begin[r]);
+  if (n_tiles) {
+    compare_static_kernel<<<grid_for(n_tiles), kBlock, 0, s>>>(st, (const uint8_t*)live,
+                                                               (const uint8_t*)golden, scratch_ptr);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  switch (finalize_block(max_region_tiles)) {
+    case 64: compare_static_finalize_kernel<64><<<st.n, 64, 0, s>>>(st, scratch_ptr, out, summary); break;
+    case 256: compare_static_finalize_kernel<256><<<st.n, 256, 0, s>>>(st, scratch_ptr, out, summary); break;
+    default: compare_static_finalize_kernel<1024><<<st.n, 1024, 0, s>>>(st, scratch_ptr, out, summary); break;
+  }
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && st.n > 1 && summary != nullptr) {
+    summary_kernel<<<1, kBlock, 0, s>>>(out, st.n, summary, nullptr, 0, nullptr);
     e = hipGetLastError();
   }
   return e;
