@@ -9,11 +9,15 @@ recorded epilogue, summary back to the host.  Inputs (snapshots, golden state, t
 resident in HBM before the timed region starts.  Prints ONE JSON line.
 
 Workloads (shapes of the five benchmark configurations):
-  jacobi          256^3 fp64 7-point Jacobi, 8 candidate variants (default)
+  large_snapshot  16 x 2 GiB regions (fp32 / bf16), 32 GiB per arena (default: the largest state
+                  that fits one GPU and the one the HBM-roofline figure is quoted on)
+  jacobi          256^3 fp64 7-point Jacobi, 8 candidate variants
   replay_small    3 x 2^20 fp32 inputs + 2^20 fp32 output, pure restore -> validate replays
   many_regions    4096 regions, 256 B .. 1 MiB, ~0.5 GiB: restore + validate the whole table
-  large_snapshot  16 x 2 GiB regions (fp32 / bf16), 32 GiB per arena
   spmv            CSR SpMV, 2^21 rows x 27 nnz, 64 launch configurations
+The default run also records short legs of the other four workloads (evaluations/s, stage rates,
+their own CPU baseline), the bandwidth yardsticks (plain copy, two-stream read) and the validation
+of states that differ from the recorded one in every element.
 """
 import argparse
 import collections
@@ -55,12 +59,12 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=None)
     p.add_argument("--warmup", type=int, default=None)
-    p.add_argument("--workload", default="jacobi",
+    p.add_argument("--workload", default="large_snapshot",
                    choices=["jacobi", "replay_small", "many_regions", "large_snapshot", "spmv"])
     p.add_argument("--inflight", type=int, default=2,
                    help="evaluations kept in flight (r3_eval_submit / r3_eval_wait); 1 = the synchronous "
                         "r3_eval_candidate")
-    p.add_argument("--no-large", action="store_true", help="skip the extra large-snapshot leg")
+    p.add_argument("--no-all-differ", action="store_true", help="skip the every-element-differs validation leg")
     p.add_argument("--no-others", action="store_true", help="skip the short legs of the other workloads")
     p.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     p.add_argument("--calibrate-copy", action="store_true",
@@ -356,22 +360,45 @@ def stage_report(rp, prof):
 
 
 def roofline(rp, stages):
-    """The dominant kernel of the path: whichever of restore / validate takes longer."""
+    """The dominant kernel of the path (whichever of restore / validate takes longer per launch), plus
+    the whole pipeline: all algorithmic bytes of one replay over the time of both stages."""
     cands = [(k, stages[k]) for k in ("restore", "validate") if k in stages]
     name, st = max(cands, key=lambda kv: kv[1]["ms"])
     kernel = "restore_kernel" if name == "restore" else "compare_kernel + compare_finalize_kernel"
     ach = st["GB/s"]
     out = {"bound": "hbm", "kernel": kernel, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
            "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(rp.name, name),
-           "algorithmic_bytes_per_launch": st["algorithmic_bytes"], "avg_launch_ms": st["ms"]}
+           "algorithmic_bytes_per_launch": st["algorithmic_bytes"], "avg_launch_ms": st["ms"],
+           "stage_fracs": {k: v["GB/s"] / HBM_PEAK_GBS for k, v in cands}}
+    if "restore+validate" in stages:
+        both = stages["restore+validate"]
+        out["pipeline"] = {"achieved": both["GB/s"], "frac": both["frac_of_hbm_peak"], "ms": both["ms"],
+                           "algorithmic_bytes": both["algorithmic_bytes"],
+                           "slowest_stage": min(cands, key=lambda kv: kv[1]["GB/s"])[0]}
     if rp.restore_bytes + rp.validate_bytes < (256 << 20):
         out["note"] = ("the working set of this workload stays in the caches and a launch lasts microseconds: "
                        "latency-bound, the fraction is not a roofline claim (evaluations/s is the figure)")
     return out
 
 
-def cpu_baseline(rp):
-    """The CPU oracle, untuned, single thread, on a bounded sample of the same workload."""
+def host_threads():
+    """Threads the CPU baseline may use: the machine's CPU share (16 for one GPU), never more than the host has."""
+    return max(1, min(16, os.cpu_count() or 1))
+
+
+def cpu_model():
+    try:
+        for ln in open("/proc/cpuinfo"):
+            if ln.startswith("model name"):
+                return ln.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(rp, budget_s=10.0):
+    """The CPU oracle, untuned, on a bounded sample of the same workload: one thread, and for the large
+    snapshot also one oracle call per host thread on disjoint chunks."""
     import numpy as np
 
     import r3_inputs as ri
@@ -394,7 +421,7 @@ def cpu_baseline(rp):
         while True:
             res = o.eval_candidate(rt, pro, ct, epi, live, sweep, 0, 1)
             evals += 1
-            if time.perf_counter() - t0 > 10.0 or evals >= 8:
+            if time.perf_counter() - t0 > budget_s or evals >= 8:
                 break
         dt = time.perf_counter() - t0
         assert res["pass"] == 1
@@ -406,7 +433,7 @@ def cpu_baseline(rp):
         rt, ct = o.make_table(c["restore_rows"]), o.make_table(c["check_rows"])
         live = c["live"].copy()
         evals, t0 = 0, time.perf_counter()
-        while time.perf_counter() - t0 < 10.0:
+        while time.perf_counter() - t0 < budget_s:
             o.eval_candidate(rt, c["prologue"], ct, c["epilogue"], live, None, 0, 1)
             evals += 1
         dt = time.perf_counter() - t0
@@ -417,7 +444,7 @@ def cpu_baseline(rp):
         t = o.make_table(c["rows"])
         live = c["live"].copy()
         evals, t0 = 0, time.perf_counter()
-        while evals < 4 and (evals == 0 or time.perf_counter() - t0 < 12.0):
+        while evals < 4 and (evals == 0 or time.perf_counter() - t0 < budget_s):
             res = o.eval_candidate(t, c["snapshot"], t, c["snapshot"], live, None, 0, 1)
             evals += 1
         dt = time.perf_counter() - t0
@@ -438,7 +465,7 @@ def cpu_baseline(rp):
             a[y_off:y_off + y_bytes] = y.astype("<f8").view(np.uint8)
             return 0
         evals, t0 = 0, time.perf_counter()
-        while evals < 4 and (evals == 0 or time.perf_counter() - t0 < 12.0):
+        while evals < 4 and (evals == 0 or time.perf_counter() - t0 < budget_s):
             o.eval_candidate(rt, c["prologue"], ct, epi, live, product, 0, 1)
             evals += 1
         dt = time.perf_counter() - t0
@@ -446,55 +473,200 @@ def cpu_baseline(rp):
                 "sample": "%d evaluations: oracle restore of the 688 MiB arena, numpy row sums as the "
                           "candidate, oracle compare of y (16 MiB)" % evals}
     if rp.name == "large_snapshot":
-        # one fp32 and one bf16 region (2 of 16, 1/8 of the bytes), downloaded from the device
-        vals = []
-        for r in (0, 8):
-            off, nb = rp.check_tbl.host[r]["offset"], rp.check_tbl.host[r]["bytes"]
-            off, nb = int(off), int(nb)
-            snap = rp.d_pro[off:off + nb].cpu().numpy()
-            gold = rp.d_epi[off:off + nb].cpu().numpy()
-            live = np.empty_like(snap)
-            row = o.make_table([(0, nb) + tuple(rp.check_tbl.host[r].tolist()[2:])])
-            t0 = time.perf_counter()
-            o.eval_candidate(row, snap, row, gold, live, None, 0, 1)
-            vals.append(time.perf_counter() - t0)
-            del snap, gold, live
-        per_eval = sum(vals) * 8.0
-        return {"value": 1.0 / per_eval, "unit": "evals/s", "cores": 1, "kind": "oracle",
-                "sample": "restore+validate of regions 0 (fp32) and 8 (bf16), 4 GiB of the 32 GiB state; "
-                          "time scaled by 8 to the whole state"}
+        return cpu_baseline_large(rp, o, np)
     return None
 
 
-def large_leg(r3, wl, ctx, torch):
-    free, _ = torch.cuda.mem_get_info()
-    if free < 110 * (1 << 30):
-        return {"skipped": "needs 96 GiB of free device memory, %.0f GiB free" % (free / 2**30)}
-    rp = Replay("large_snapshot", r3, wl, ctx, torch)
-    dt, prof = timed_run(rp, 3, 1)
-    st = stage_report(rp, prof)
-    out = {"workload": rp.desc, "steps": 3, "ms_per_step": dt / 3 * 1e3, "stages": st,
-           "roofline": roofline(rp, st), "record_path": record_path_leg(rp, reps=3)}
-    del rp
+def cpu_baseline_large(rp, o, np):
+    """Regions 0 (fp32) and 8 (bf16) of the 16, i.e. 4 GiB of the 32 GiB state, downloaded from the device.
+    T = 1: the oracle's restore + compare on each of the two regions, one after the other.  T = host
+    threads: the same bytes cut into 16 chunks of 256 MiB, each chunk a region of its own, one plain oracle
+    call per chunk on a pool of T threads (the oracle itself stays single-threaded; counts add, indices
+    take the minimum, maxima the maximum).  Times are scaled by 8 to the whole state."""
+    import concurrent.futures as cf
+    picked = (0, 8)
+    host = []
+    for r in picked:
+        row = rp.check_tbl.host[r]
+        off, nb = int(row["offset"]), int(row["bytes"])
+        host.append((rp.d_pro[off:off + nb].cpu().numpy(), rp.d_epi[off:off + nb].cpu().numpy(),
+                     tuple(row.tolist()[2:]), nb))
+    scale = 16.0 / len(picked)
+    bytes_per_eval = 4.0 * sum(h[3] for h in host) * scale       # restore 2 B/B + compare 2 B/B
+    # T = 1
+    t_single, counts = 0.0, []
+    for snap, gold, tail, nb in host:
+        live = np.empty_like(snap)
+        tbl = o.make_table([(0, nb) + tail])
+        t0 = time.perf_counter()
+        res = o.eval_candidate(tbl, snap, tbl, gold, live, None, 0, 1)
+        t_single += time.perf_counter() - t0
+        counts.append(int(res["total_mismatch"]))
+        del live
+    per_eval = t_single * scale
+    out = {"value": 1.0 / per_eval, "unit": "evals/s", "cores": 1, "kind": "oracle", "cpu": cpu_model(),
+           "GB/s": bytes_per_eval / per_eval / 1e9,
+           "sample": "restore+validate of regions 0 (fp32) and 8 (bf16), 4 GiB of the 32 GiB state (%.1f s of "
+                     "CPU); time scaled by 8 to the whole state" % t_single}
+    # T = host threads
+    T = host_threads()
+    jobs = []
+    for snap, gold, tail, nb in host:
+        step = nb // 8
+        for k in range(8):
+            jobs.append((snap[k * step:(k + 1) * step], gold[k * step:(k + 1) * step],
+                         o.make_table([(0, step) + tail])))
+    lives = [np.empty_like(j[0]) for j in jobs]
+
+    def one(i):
+        snap, gold, tbl = jobs[i]
+        return int(o.eval_candidate(tbl, snap, tbl, gold, lives[i], None, 0, 1)["total_mismatch"])
+    t0 = time.perf_counter()
+    with cf.ThreadPoolExecutor(max_workers=T) as pool:
+        chunk_counts = list(pool.map(one, range(len(jobs))))
+    t_threads = time.perf_counter() - t0
+    assert sum(chunk_counts) == sum(counts), "chunked oracle run disagrees with the whole-region run"
+    per_eval_t = t_threads * scale
+    out["threads"] = {"value": 1.0 / per_eval_t, "unit": "evals/s", "cores": T, "GB/s": bytes_per_eval / per_eval_t / 1e9,
+                      "sample": "the same 4 GiB as 16 chunks of 256 MiB, one single-thread oracle call per chunk on "
+                                "%d host threads (%.1f s); time scaled by 8" % (T, t_threads)}
+    return out
+
+
+def ceilings_leg(wl, torch, reps=10):
+    """What this GPU gives the plainest kernels with the replay path's traffic shapes: a copy (one read
+    and one write stream) and a two-stream read of 2 GiB per stream, 16-byte accesses, no table, no
+    arithmetic beyond an XOR.  The best shape of each is the yardstick the stage rates are held against."""
+    nbytes = 2 << 30
+    a = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    b = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    a.fill_(1)
+    b.fill_(1)
+    sink = torch.zeros(4, dtype=torch.uint8, device="cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    out = {"bytes_per_stream": nbytes, "shapes": {}}
+    for kib in (1, 4, 16):
+        ms_c = timed(lambda: wl.yard_copy(a, b, nbytes, kib, stream))
+        ms_r = timed(lambda: wl.yard_read2(a, b, nbytes, sink, kib, stream))
+        out["shapes"]["%d KiB per wavefront" % kib] = {"copy_GBs": 2 * nbytes / ms_c / 1e6,
+                                                       "read2_GBs": 2 * nbytes / ms_r / 1e6}
+    out["copy_GBs"] = max(v["copy_GBs"] for v in out["shapes"].values())
+    out["read2_GBs"] = max(v["read2_GBs"] for v in out["shapes"].values())
+    del a, b
     torch.cuda.empty_cache()
     return out
 
 
-def other_legs(r3, wl, ctx, torch, skip, inflight, defaults):
-    """Evaluations/s and stage rates of the workloads that are neither the headline one nor the
-    large snapshot, so that one run records all five."""
+def against_ceilings(stages, ceil):
     out = {}
-    for name in ("replay_small", "many_regions", "spmv"):
+    if "restore" in stages:
+        out["restore_vs_copy"] = stages["restore"]["GB/s"] / ceil["copy_GBs"]
+    if "validate" in stages:
+        out["validate_vs_read2"] = stages["validate"]["GB/s"] / ceil["read2_GBs"]
+    return out
+
+
+def all_differ_leg(r3, ctx, torch, nbytes=256 << 20, reps=10):
+    """Validation of a state that differs from the recorded one in EVERY element by one bit-pattern step
+    (the pattern of a numerically equivalent rewrite under the relaxed criterion, Section V-C): one
+    region of 256 MiB per element type, tolerance mode, rates incl. the finalize launch."""
+    import r3_inputs as ri
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(4711)
+    kinds = [("fp64", ri.F64, torch.float64, torch.int64, 1e-12, 0.0),
+             ("fp32", ri.F32, torch.float32, torch.int32, 1e-5, 1e-7),
+             ("bf16", ri.BF16, torch.bfloat16, torch.int16, 1e-2, 1e-3),
+             ("fp16", ri.F16, torch.float16, torch.int16, 1e-2, 1e-3),
+             ("int32", ri.I32, None, torch.int32, 0.0, 1.0),
+             ("u8", ri.U8, None, torch.uint8, 0.0, 1.0)]
+    d_out = torch.zeros(40, dtype=torch.uint8, device="cuda:0")
+    d_sum = torch.zeros(40, dtype=torch.uint8, device="cuda:0")
+    out = {}
+    for name, dt, fdt, idt, rtol, atol in kinds:
+        es = ri.ELEM_SIZE[dt]
+        n = nbytes // es
+        gold = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+        if fdt is not None:
+            for lo in range(0, n, 1 << 26):
+                hi = min(n, lo + (1 << 26))
+                gold.view(fdt)[lo:hi] = torch.randn(hi - lo, generator=gen, device="cuda:0",
+                                                    dtype=torch.float32).to(fdt)
+        else:
+            gold.copy_(torch.randint(0, 256, (nbytes,), generator=gen, device="cuda:0", dtype=torch.uint8))
+            if dt == ri.I32:
+                gold.view(torch.int32).bitwise_and_(0x3FFFFFFF)
+        live = gold.clone()
+        live.view(idt).add_(1)                     # every element one pattern step away
+        tbl = r3.Table(ctx, [(0, nbytes, dt, ri.TOL, rtol, atol)], nbytes)
+
+        def run():
+            r3.r3_compare(ctx, tbl, live, gold, d_out, d_sum)
+        run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        res = r3.results_to_numpy(d_out, 1)[0]
+        out[name] = {"ms": ms, "algorithmic_bytes": 2 * nbytes, "GB/s": 2 * nbytes / ms / 1e6,
+                     "frac_of_hbm_peak": 2 * nbytes / ms / 1e6 / HBM_PEAK_GBS,
+                     "mismatch_count": int(res["mismatch_count"]), "max_rel_err": float(res["max_rel_err"])}
+        # the same region with nothing different, for comparison
+        live.copy_(gold)
+        run()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name]["identical_GB/s"] = 2 * nbytes / (e0.elapsed_time(e1) / reps) / 1e6
+        del tbl, live, gold
+        torch.cuda.empty_cache()
+    return out
+
+
+def other_legs(r3, wl, ctx, torch, skip, inflight, defaults, ceil, with_cpu):
+    """Evaluations/s, stage rates and the oracle's rate for the workloads that are not the headline one,
+    so that one run records all five."""
+    out = {}
+    for name in ("jacobi", "replay_small", "many_regions", "spmv", "large_snapshot"):
         if name == skip:
             continue
+        if name == "large_snapshot":
+            free, _ = torch.cuda.mem_get_info()
+            if free < 110 * (1 << 30):
+                out[name] = {"skipped": "needs 96 GiB of free device memory, %.0f GiB free" % (free / 2**30)}
+                continue
         rp = Replay(name, r3, wl, ctx, torch)
         steps, warmup = defaults[name]
-        steps = max(64, steps // 2)
+        if name != "large_snapshot":
+            steps = max(64, steps // 2)
         dt, prof = timed_run(rp, steps, warmup, inflight)
         st = stage_report(rp, prof)
         leg = {"workload": rp.desc, "value": steps / dt, "unit": "evals/s", "steps": steps,
-               "ms_per_step": dt / steps * 1e3, "evaluations_in_flight": inflight, "stages": st}
-        if name == "spmv":
+               "ms_per_step": dt / steps * 1e3, "evaluations_in_flight": inflight, "stages": st,
+               "roofline": roofline(rp, st), "vs_ceilings": against_ceilings(st, ceil)}
+        if inflight > 1:
+            dt1, _ = timed_run(rp, steps, warmup, 1)
+            leg["synchronous"] = {"value": steps / dt1, "unit": "evals/s", "ms_per_step": dt1 / steps * 1e3}
+        if with_cpu:
+            leg["cpu_baseline"] = cpu_baseline(rp, budget_s=3.0)
+        if name in ("jacobi", "spmv"):
             leg["write_set_replay"] = writeset_leg(rp, steps, warmup, inflight)
         out[name] = leg
         del rp
@@ -519,9 +691,18 @@ def main():
     wl.lib()
     ctx = r3.Context(0)
     defaults = {"jacobi": (200, 16), "replay_small": (2000, 100), "many_regions": (200, 10),
-                "large_snapshot": (5, 1), "spmv": (128, 8)}
+                "large_snapshot": (20, 2), "spmv": (128, 8)}
     steps = a.steps if a.steps is not None else defaults[a.workload][0]
     warmup = a.warmup if a.warmup is not None else defaults[a.workload][1]
+    if not 1 <= a.inflight <= 8:
+        print("--inflight must be 1 .. 8", file=sys.stderr)
+        sys.exit(2)
+    if a.workload == "large_snapshot":
+        free, _ = torch.cuda.mem_get_info()
+        if free < 110 * (1 << 30):
+            print("the large snapshot needs 96 GiB of free device memory, %.0f GiB free" % (free / 2**30),
+                  file=sys.stderr)
+            sys.exit(2)
 
     if a.calibrate_copy:
         buf = torch.zeros(2 << 30, dtype=torch.uint8, device="cuda:0")
@@ -532,37 +713,36 @@ def main():
         del buf
         torch.cuda.empty_cache()
 
+    ceil = ceilings_leg(wl, torch)
     rp = Replay(a.workload, r3, wl, ctx, torch)
-    if not 1 <= a.inflight <= 8:
-        print("--inflight must be 1 .. 8", file=sys.stderr)
-        sys.exit(2)
     dt, prof = timed_run(rp, steps, warmup, a.inflight)
     stages = stage_report(rp, prof)
     line = {
         "metric": "candidate evals/sec per kernel; restore+compare GB/s as % of HBM peak",
         "value": steps / dt, "unit": "evals/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": dt / steps * 1e3, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f64" if a.workload in ("jacobi", "spmv") else "u8",
-        "data": "synthetic",
+        "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": "%s: %s" % (a.workload, rp.desc), "evaluations_in_flight": a.inflight},
         "roofline": roofline(rp, stages),
         "stages": stages,
+        "ceilings": ceil,
+        "vs_ceilings": against_ceilings(stages, ceil),
     }
     if a.inflight > 1:
         dt1, _ = timed_run(rp, steps, warmup, 1)
         line["synchronous"] = {"value": steps / dt1, "unit": "evals/s", "ms_per_step": dt1 / steps * 1e3,
                                "note": "the same evaluations through r3_eval_candidate, one at a time"}
-    cpu = None if a.no_cpu else cpu_baseline(rp)
-    line["cpu_baseline"] = cpu
-    line["record_path"] = record_path_leg(rp)
+    line["cpu_baseline"] = None if a.no_cpu else cpu_baseline(rp)
+    line["record_path"] = record_path_leg(rp, reps=3 if a.workload == "large_snapshot" else 10)
     if a.workload in ("jacobi", "spmv"):
         line["write_set_replay"] = writeset_leg(rp, steps, warmup, a.inflight)
     del rp
     torch.cuda.empty_cache()
+    if not a.no_all_differ:
+        line["all_differ"] = all_differ_leg(r3, ctx, torch)
     if not a.no_others:
-        line["other_workloads"] = other_legs(r3, wl, ctx, torch, a.workload, a.inflight, defaults)
-    if a.workload != "large_snapshot" and not a.no_large:
-        line["large_snapshot"] = large_leg(r3, wl, ctx, torch)
+        line["other_workloads"] = other_legs(r3, wl, ctx, torch, a.workload, a.inflight, defaults, ceil,
+                                             not a.no_cpu)
     print(json.dumps(line))
 
 

@@ -37,6 +37,16 @@ int r3w_jacobi_launch(void* user, void* d_live, void* stream);
 int r3w_copy_launch(void* user, void* d_live, void* stream);
 int r3w_spmv_launch(void* user, void* d_live, void* stream);
 int r3w_failing_launch(void* user, void* d_live, void* stream);
+
+// Bandwidth yardsticks: the plainest kernels that move bytes the way the replay path does, to
+// measure what this GPU gives a copy (one read stream, one write stream) and a two-stream
+// read, with no table, no checksum and no compare around them.  bytes must be a multiple of
+// kib_per_wave KiB; kib_per_wave in {1, 4, 16}: each wavefront (one 64-thread block) moves that
+// many KiB with 16-byte accesses per lane.  d_sink: 4 bytes of device memory that is only
+// written if the data XOR to a magic value (keeps the loads alive).
+int r3w_yard_copy(const void* d_src, void* d_dst, uint64_t bytes, uint32_t kib_per_wave, void* stream);
+int r3w_yard_read2(const void* d_a, const void* d_b, uint64_t bytes, uint32_t kib_per_wave, void* d_sink,
+                   void* stream);
 }
 
 namespace {
@@ -66,6 +76,39 @@ __global__ void jacobi_kernel(const double* __restrict__ in, double* __restrict_
 __global__ void plain_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, uint64_t n) {
   const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
   for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+typedef uint32_t yard_vec __attribute__((ext_vector_type(4)));
+
+template <int VPL>  // 16-byte vectors per lane
+__global__ __launch_bounds__(64) void yard_copy_kernel(const yard_vec* __restrict__ src,
+                                                       yard_vec* __restrict__ dst) {
+  const uint64_t at = (uint64_t)blockIdx.x * 64 * VPL + threadIdx.x;
+  yard_vec r[VPL];
+#pragma unroll
+  for (int u = 0; u < VPL; ++u) r[u] = __builtin_nontemporal_load(src + at + 64 * u);
+#pragma unroll
+  for (int u = 0; u < VPL; ++u) __builtin_nontemporal_store(r[u], dst + at + 64 * u);
+}
+
+template <int VPL>
+__global__ __launch_bounds__(64) void yard_read2_kernel(const yard_vec* __restrict__ a,
+                                                        const yard_vec* __restrict__ b, uint32_t* sink) {
+  const uint64_t at = (uint64_t)blockIdx.x * 64 * VPL + threadIdx.x;
+  uint32_t acc = 0;
+  constexpr int STEP = VPL < 4 ? VPL : 4;  // vectors in flight per stream
+  for (int v = 0; v < VPL; v += STEP) {
+    yard_vec r[STEP], q[STEP];
+#pragma unroll
+    for (int u = 0; u < STEP; ++u) {
+      r[u] = __builtin_nontemporal_load(a + at + 64 * (v + u));
+      q[u] = __builtin_nontemporal_load(b + at + 64 * (v + u));
+    }
+#pragma unroll
+    for (int u = 0; u < STEP; ++u)
+      acc |= (r[u].x ^ q[u].x) | (r[u].y ^ q[u].y) | (r[u].z ^ q[u].z) | (r[u].w ^ q[u].w);
+  }
+  if (acc == 0x12345678u) *sink = acc;
 }
 
 template <int LANES>  // lanes that share one row
@@ -173,6 +216,42 @@ int r3w_spmv_launch(void* user, void* d_live, void* stream) {
     default: spmv_serial_kernel<2><<<grid, a->block, 0, s>>>(rp, ci, v, x, y, a->rows); break;
   }
 #undef SHARED
+  return hipGetLastError() == hipSuccess ? 0 : 5;
+}
+
+int r3w_yard_copy(const void* d_src, void* d_dst, uint64_t bytes, uint32_t kib_per_wave, void* stream) {
+  if (d_src == nullptr || d_dst == nullptr || ((uintptr_t)d_src | (uintptr_t)d_dst) & 15) return 1;
+  if ((kib_per_wave != 1 && kib_per_wave != 4 && kib_per_wave != 16) || bytes % (kib_per_wave * 1024ull)) return 2;
+  const uint64_t blocks = bytes / (kib_per_wave * 1024ull);
+  if (blocks == 0) return 0;
+  if (blocks > 0x7FFFFFFFull) return 3;
+  const yard_vec* s = static_cast<const yard_vec*>(d_src);
+  yard_vec* d = static_cast<yard_vec*>(d_dst);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  switch (kib_per_wave) {
+    case 1: yard_copy_kernel<1><<<(uint32_t)blocks, 64, 0, st>>>(s, d); break;
+    case 4: yard_copy_kernel<4><<<(uint32_t)blocks, 64, 0, st>>>(s, d); break;
+    default: yard_copy_kernel<16><<<(uint32_t)blocks, 64, 0, st>>>(s, d); break;
+  }
+  return hipGetLastError() == hipSuccess ? 0 : 5;
+}
+
+int r3w_yard_read2(const void* d_a, const void* d_b, uint64_t bytes, uint32_t kib_per_wave, void* d_sink,
+                   void* stream) {
+  if (d_a == nullptr || d_b == nullptr || d_sink == nullptr || ((uintptr_t)d_a | (uintptr_t)d_b) & 15) return 1;
+  if ((kib_per_wave != 1 && kib_per_wave != 4 && kib_per_wave != 16) || bytes % (kib_per_wave * 1024ull)) return 2;
+  const uint64_t blocks = bytes / (kib_per_wave * 1024ull);
+  if (blocks == 0) return 0;
+  if (blocks > 0x7FFFFFFFull) return 3;
+  const yard_vec* a = static_cast<const yard_vec*>(d_a);
+  const yard_vec* b = static_cast<const yard_vec*>(d_b);
+  uint32_t* sink = static_cast<uint32_t*>(d_sink);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  switch (kib_per_wave) {
+    case 1: yard_read2_kernel<1><<<(uint32_t)blocks, 64, 0, st>>>(a, b, sink); break;
+    case 4: yard_read2_kernel<4><<<(uint32_t)blocks, 64, 0, st>>>(a, b, sink); break;
+    default: yard_read2_kernel<16><<<(uint32_t)blocks, 64, 0, st>>>(a, b, sink); break;
+  }
   return hipGetLastError() == hipSuccess ? 0 : 5;
 }
 

@@ -60,6 +60,25 @@ def plain_copy(d_arena, src_off, dst_off, nbytes, stream=0):
         raise RuntimeError("plain copy launch failed: %d" % rc)
 
 
+def yard_copy(d_src, d_dst, nbytes, kib_per_wave=1, stream=0):
+    """Plain copy yardstick: nbytes from d_src to d_dst (uint8 CUDA tensors)."""
+    f = lib().r3w_yard_copy
+    f.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p]
+    rc = f(d_src.data_ptr(), d_dst.data_ptr(), nbytes, kib_per_wave, stream)
+    if rc:
+        raise RuntimeError("yard copy launch failed: %d" % rc)
+
+
+def yard_read2(d_a, d_b, nbytes, d_sink, kib_per_wave=4, stream=0):
+    """Two-stream read yardstick: reads nbytes of d_a and of d_b."""
+    f = lib().r3w_yard_read2
+    f.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p,
+                  ctypes.c_void_p]
+    rc = f(d_a.data_ptr(), d_b.data_ptr(), nbytes, kib_per_wave, d_sink.data_ptr(), stream)
+    if rc:
+        raise RuntimeError("yard read2 launch failed: %d" % rc)
+
+
 def failing_launch():
     return _addr("r3w_failing_launch")
 
