@@ -25,8 +25,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kUnroll = 4;                       // 16-byte loads in flight per lane and stream
 constexpr uint64_t kVecKeyStep = 128ull * kPhi;  // 64 lanes * 2 words per 16-byte vector
 constexpr double kInf = __builtin_huge_val();
-constexpr double kGateShrink = 0x1.ffffffffffff8p-1;  // 1 - 2^-50
-constexpr double kGateFloor = 0x1p-1000;
 
 __device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
 
@@ -386,7 +384,8 @@ struct Acc {
   uint32_t first;  // smallest mismatching element index inside the tile, ~0u if none
   double max_abs;
   double max_rel;
-  double gate;     // wavefront-uniform lower bound of the running max_rel, shrunk by 2^-50
+  double top;      // a lower bound of the tile's final max_rel: this lane's own maximum or the
+                   // wavefront's at its last exchange, whichever is larger
   uint64_t cks;
 };
 
@@ -415,12 +414,40 @@ __device__ __forceinline__ double to_f64(uint64_t bits, uint32_t dtype) {
   }
 }
 
-// One element whose bit patterns differ.  Returns true when this lane's max_rel grew.
-//
-// The quotient d/|G| is needed only when it can exceed the running maximum.  With
-// gate <= max_rel*(1-2^-50) known for the whole wavefront and p = fl(gate*|G|) a normal
-// number, d <= p implies d < max_rel*|G| exactly, hence fl(d/|G|) <= max_rel: the divide
-// is skipped.  Any other case (p tiny, zero, NaN) takes the divide.
+// Can the quotient d/|G| exceed `top`?  The quotient is needed only when it can raise the
+// running maximum of the relative error.  With ph = fl(top*|G|) and pl = fma(top, |G|, -ph)
+// the product top*|G| equals ph + pl exactly (pl cannot underflow while ph >= 2^-900), and
+// u = fl(fl(d - ph) - pl) has the sign of d - top*|G|: if d and ph are within a factor of two
+// the first difference is exact and the second keeps the sign; otherwise |d - ph| >= ph/2
+// dwarfs pl.  So
+//   ph >= 2^-900 and u <= 0   =>   d <= top*|G|   =>   fl(d/|G|) <= top,
+// and the divide can be skipped; equal quotients (ties, frequent with 8- and 16-bit types)
+// are skipped as well.  d == 0 never raises anything.  Everything else (ph tiny, zero or NaN,
+// d NaN or infinite, overflow of ph) answers "maybe": an answer "no" therefore also says that
+// d is finite, hence that both inputs are.  Written with bitwise operators on purpose: the
+// compiler must not turn the tests into branches.
+constexpr double kTopFloor = 0x1p-900;
+__device__ __forceinline__ bool may_raise_max_rel(double d, double aG, double top) {
+  const double ph = top * aG;
+  const double pl = __builtin_fma(top, aG, -ph);
+  const double u = (d - ph) - pl;
+  const bool below = (ph >= kTopFloor) & (u <= 0.0);
+  return !(below | (d == 0.0));
+}
+
+// The relative error of one element whose quotient may raise the maximum.  Returns true when
+// this lane's max_rel grew.
+__device__ __forceinline__ bool raise_max_rel(double d, double G, double aG, Acc& a) {
+  const double r = (G == 0.0) ? 0.0 : d / aG;
+  if (r > a.max_rel) {
+    a.max_rel = r;
+    a.top = r > a.top ? r : a.top;
+    return true;
+  }
+  return false;
+}
+
+// One element whose bit patterns differ (tails and regions that are not 16-byte aligned).
 __device__ __forceinline__ bool differing_elem(uint64_t cb, uint64_t gb, uint32_t idx,
                                                const ElemKind& k, Acc& a) {
   const double C = to_f64(cb, k.dtype), G = to_f64(gb, k.dtype);
@@ -432,6 +459,7 @@ __device__ __forceinline__ bool differing_elem(uint64_t cb, uint64_t gb, uint32_
     mis = true;
     if (!(a.max_rel == kInf)) {
       a.max_rel = kInf;
+      a.top = kInf;
       grew = true;
     }
   } else {
@@ -443,14 +471,7 @@ __device__ __forceinline__ bool differing_elem(uint64_t cb, uint64_t gb, uint32_
     } else {
       mis = true;
     }
-    const double p = a.gate * aG;
-    if (!(d <= p && p >= kGateFloor)) {
-      const double r = (G == 0.0) ? 0.0 : d / aG;
-      if (r > a.max_rel) {
-        a.max_rel = r;
-        grew = true;
-      }
-    }
+    if (may_raise_max_rel(d, aG, a.top)) grew = raise_max_rel(d, G, aG, a);
   }
   a.max_abs = d > a.max_abs ? d : a.max_abs;
   a.count += mis ? 1u : 0u;
@@ -460,9 +481,8 @@ __device__ __forceinline__ bool differing_elem(uint64_t cb, uint64_t gb, uint32_
 }
 
 // One 64-bit word of live (wc) and golden (wg) data holding `nvalid` elements; idx = tile
-// index of its first element.  The element loop is deliberately not unrolled: this path is
-// rare in bandwidth-bound runs and the kernel has to stay small enough for the instruction
-// cache when regions of different element types are interleaved.
+// index of its first element.  The element loop is deliberately not unrolled: this path only
+// serves tails and unaligned regions.
 __device__ __forceinline__ bool differing_word(uint64_t wc, uint64_t wg, uint32_t nvalid,
                                                uint32_t idx, const ElemKind& k, Acc& a) {
   if (wc == wg) return false;
@@ -482,12 +502,12 @@ __device__ __forceinline__ bool differing_word(uint64_t wc, uint64_t wg, uint32_
 
 // ---- whole 16-byte vectors, specialised per element type ------------------------------
 // Candidates that are numerically equivalent but not bit-identical differ almost
-// everywhere, so this path matters too.  Measured alternatives on 128 MiB of fp32 that
-// differs in every element: this per-lane form 3.1 TB/s; a form that takes every decision
-// for the whole wavefront (quick pass without divides, careful pass with selects) 1.7 TB/s,
-// because it is bound by dependent fp64 latency, not by issue rate; sharing the running
-// maximum between tiles through a per-region slot in memory 1.5 TB/s, because thousands of
-// wavefronts then update one address with device-scope atomics.
+// everywhere, so this path matters as much as the bit-equal one.  A vector is handled in
+// chunks of four elements (two for 8-byte elements).  The common case of a chunk needs no
+// branch and no divide: every element's error is finite and provably cannot raise max_rel;
+// then counting, the first index and max_abs are plain arithmetic.  A chunk in which any
+// lane of the wavefront sees anything else (a possible new maximum, NaN, infinity) is redone
+// element by element with the full rules.
 template <int DT> struct Elem;
 template <> struct Elem<R3_U8>   { static constexpr int size = 1; static constexpr bool is_float = false; };
 template <> struct Elem<R3_F32>  { static constexpr int size = 4; static constexpr bool is_float = true; };
@@ -506,12 +526,26 @@ __device__ __forceinline__ double to_f64_t(uint64_t bits) {
   return bits_d(bits);
 }
 
-// One element, equal or not.  Equal finite patterns give d = 0 and fall through every
-// test; the only branches are the rare ones (non-finite values, a possible new maximum of
-// the relative error).
+// Bit pattern of element e of a 16-byte vector.
 template <int DT>
-__device__ __forceinline__ bool vec_elem(uint64_t cb, uint64_t gb, uint32_t idx, const ElemKind& k,
-                                         Acc& a) {
+__device__ __forceinline__ uint64_t elem_bits(const u32x4& v, int e) {
+  constexpr int ES = Elem<DT>::size;
+  if constexpr (ES == 8) {
+    return ((uint64_t)v[2 * e + 1] << 32) | v[2 * e];
+  } else if constexpr (ES == 4) {
+    return v[e];
+  } else if constexpr (ES == 2) {
+    return (v[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+  } else {
+    return (v[e >> 2] >> (8 * (e & 3))) & 0xFFu;
+  }
+}
+
+// One element under the full rules, equal or not (the careful path of a chunk).  Returns
+// whether this lane's max_rel grew.
+template <int DT>
+__device__ __forceinline__ bool careful_elem(uint64_t cb, uint64_t gb, uint32_t idx, const ElemKind& k,
+                                             Acc& a) {
   const bool differ = cb != gb;
   const double C = to_f64_t<DT>(cb), G = to_f64_t<DT>(gb);
   const double aG = __builtin_fabs(G);
@@ -526,6 +560,7 @@ __device__ __forceinline__ bool vec_elem(uint64_t cb, uint64_t gb, uint32_t idx,
       rel_done = true;
       if (!(a.max_rel == kInf)) {
         a.max_rel = kInf;
+        a.top = kInf;
         grew = true;
       }
     }
@@ -538,16 +573,7 @@ __device__ __forceinline__ bool vec_elem(uint64_t cb, uint64_t gb, uint32_t idx,
   } else {
     mis = differ;
   }
-  if (!rel_done && d != 0.0) {
-    const double p = a.gate * aG;
-    if (!(d <= p && p >= kGateFloor)) {
-      const double r = (G == 0.0) ? 0.0 : d / aG;
-      if (r > a.max_rel) {
-        a.max_rel = r;
-        grew = true;
-      }
-    }
-  }
+  if (!rel_done && may_raise_max_rel(d, aG, a.top)) grew |= raise_max_rel(d, G, aG, a);
   a.max_abs = d > a.max_abs ? d : a.max_abs;
   a.count += mis ? 1u : 0u;
   const uint32_t cand = mis ? idx : 0xFFFFFFFFu;
@@ -555,53 +581,128 @@ __device__ __forceinline__ bool vec_elem(uint64_t cb, uint64_t gb, uint32_t idx,
   return grew;
 }
 
-template <int DT>
-__device__ __forceinline__ bool vec_word(uint64_t wc, uint64_t wg, uint32_t idx, const ElemKind& k,
-                                         Acc& a) {
-  constexpr int ES = Elem<DT>::size;
-  constexpr int EPW = 8 / ES;
-  bool grew = false;
-  if (wc == wg) return false;
-  if constexpr (ES == 8) {
-    grew = vec_elem<DT>(wc, wg, idx, k, a);
-  } else {
-    constexpr uint64_t mask = (1ull << (8 * ES)) - 1;
-    constexpr int kUnrollElems = EPW > 2 ? 2 : EPW;  // full unrolling of 8 byte elements costs 50 VGPRs
-#pragma unroll kUnrollElems
-    for (int e = 0; e < EPW; ++e)
-      grew |= vec_elem<DT>((wc >> (8 * ES * e)) & mask, (wg >> (8 * ES * e)) & mask, idx + e, k, a);
-  }
-  return grew;
-}
-
-// Per lane; returns whether this lane's max_rel grew.
-template <int DT>
-__device__ __forceinline__ bool vec_both(u32x4 c, u32x4 g, uint32_t idx, const ElemKind& k, Acc& a) {
-  constexpr int EPW = 8 / Elem<DT>::size;
-  bool grew = vec_word<DT>(((uint64_t)c.y << 32) | c.x, ((uint64_t)g.y << 32) | g.x, idx, k, a);
-  grew |= vec_word<DT>(((uint64_t)c.w << 32) | c.z, ((uint64_t)g.w << 32) | g.z, idx + EPW, k, a);
-  return grew;
-}
-
-__device__ __forceinline__ bool differing_vec(u32x4 c, u32x4 g, uint32_t idx, const ElemKind& k, Acc& a) {
-  switch (k.dtype) {  // uniform across the wavefront
-    case R3_U8: return vec_both<R3_U8>(c, g, idx, k, a);
-    case R3_F32: return vec_both<R3_F32>(c, g, idx, k, a);
-    case R3_F64: return vec_both<R3_F64>(c, g, idx, k, a);
-    case R3_I32: return vec_both<R3_I32>(c, g, idx, k, a);
-    case R3_BF16: return vec_both<R3_BF16>(c, g, idx, k, a);
-    default: return vec_both<R3_F16>(c, g, idx, k, a);
-  }
-}
-
-// The wavefront-wide gate: max_rel of all lanes, shrunk.  Called by all lanes.
-__device__ __forceinline__ void refresh_gate(Acc& a) {
+// The wavefront shares its largest max_rel.  Called by all lanes (uniform control flow).
+__device__ __forceinline__ void refresh_top(Acc& a) {
   const double m = bits_d(dpp_max(dbits(a.max_rel)));
-  const double gte = m * kGateShrink;
-  a.gate = gte > a.gate ? gte : a.gate;
+  a.top = m > a.top ? m : a.top;
 }
-__device__ __forceinline__ void refresh_gate_if(bool grew, Acc& a) {
-  if (__builtin_amdgcn_ballot_w64(grew) != 0) refresh_gate(a);
+__device__ __forceinline__ void refresh_top_if(bool grew, Acc& a) {
+  if (__builtin_amdgcn_ballot_w64(grew) != 0) refresh_top(a);
+}
+
+// A vector is consumed from its low end: drop its first `BYTES` bytes (4, 8 or 16).
+template <int BYTES>
+__device__ __forceinline__ void drop_front(u32x4& v) {
+  if constexpr (BYTES == 4) {
+    v = u32x4{v.y, v.z, v.w, 0};
+  } else if constexpr (BYTES == 8) {
+    v = u32x4{v.z, v.w, 0, 0};
+  } else {
+    v = u32x4{0, 0, 0, 0};
+  }
+}
+
+// First element of a vector, and the vector without it.
+template <int DT>
+__device__ __forceinline__ uint64_t pop_elem(u32x4& v) {
+  constexpr int ES = Elem<DT>::size;
+  uint64_t bits;
+  if constexpr (ES == 8) {
+    bits = ((uint64_t)v.y << 32) | v.x;
+    drop_front<8>(v);
+  } else if constexpr (ES == 4) {
+    bits = v.x;
+    drop_front<4>(v);
+  } else {  // the chunks of 1- and 2-byte elements fit the first two dwords
+    uint64_t w = ((uint64_t)v.y << 32) | v.x;
+    bits = w & ((1ull << (8 * ES)) - 1);
+    w >>= 8 * ES;
+    v.x = (uint32_t)w;
+    v.y = (uint32_t)(w >> 32);
+  }
+  return bits;
+}
+
+// The first N elements of the vectors c and g; idx = tile index of the first.  All lanes take
+// part (uniform control flow).
+template <int DT, int N>
+__device__ __forceinline__ void compare_chunk(const u32x4& c, const u32x4& g, uint32_t idx,
+                                              const ElemKind& k, Acc& a) {
+  uint64_t cb[N], gb[N];
+  double aG[N], d[N];
+  bool need = false;
+#pragma unroll
+  for (int e = 0; e < N; ++e) {
+    cb[e] = elem_bits<DT>(c, e);
+    gb[e] = elem_bits<DT>(g, e);
+    const double C = to_f64_t<DT>(cb[e]), G = to_f64_t<DT>(gb[e]);
+    aG[e] = __builtin_fabs(G);
+    d[e] = __builtin_fabs(C - G);
+    need |= may_raise_max_rel(d[e], aG[e], a.top);
+  }
+  if (__builtin_amdgcn_ballot_w64(need) != 0) {
+    // The careful path: element by element under the full rules, one copy of the code (it
+    // runs while a tile's max_rel is still rising, and for NaN / infinity).
+    u32x4 cw = c, gw = g;
+    bool grew = false;
+#pragma unroll 1
+    for (uint32_t e = 0; e < (uint32_t)N; ++e) {
+      const uint64_t ce = pop_elem<DT>(cw), ge = pop_elem<DT>(gw);
+      grew |= careful_elem<DT>(ce, ge, idx + e, k, a);
+    }
+    refresh_top_if(grew, a);
+    return;
+  }
+  // Every d here is finite (an infinite or NaN error never passes the test above), so both
+  // inputs are finite and the plain predicate applies.
+  bool mis[N];
+  if (k.tol) {
+#pragma unroll
+    for (int e = 0; e < N; ++e) {
+      const double t = k.rtol * aG[e];
+      const double thr = k.atol + t;
+      mis[e] = d[e] > thr;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < N; ++e) mis[e] = cb[e] != gb[e];
+  }
+  bool any = false;
+#pragma unroll
+  for (int e = 0; e < N; ++e) {
+    any |= mis[e];
+    a.max_abs = __builtin_fmax(a.max_abs, d[e]);
+  }
+  // a lane's indices only grow, so its first mismatch is the one that ends first == ~0u
+  if (__builtin_amdgcn_ballot_w64(any & (a.first == 0xFFFFFFFFu)) != 0) {
+    if (any & (a.first == 0xFFFFFFFFu)) {
+      uint32_t f = 0xFFFFFFFFu;
+#pragma unroll
+      for (int e = N - 1; e >= 0; --e) f = mis[e] ? idx + e : f;
+      a.first = f;
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < N; ++e) a.count += mis[e] ? 1u : 0u;
+}
+
+// One whole vector per lane; idx = tile index of the vector's first element.  The chunks of
+// a vector go through one copy of the code.
+template <int DT>
+__device__ __forceinline__ void compare_vector(u32x4 c, u32x4 g, uint32_t idx, const ElemKind& k, Acc& a) {
+  constexpr int ES = Elem<DT>::size;
+  constexpr int N = ES == 8 ? 2 : 4;         // elements per chunk
+  constexpr int CHUNKS = 16 / (ES * N);      // 1, 1, 2, 4 for 8-, 4-, 2-, 1-byte elements
+  if constexpr (CHUNKS == 1) {
+    compare_chunk<DT, N>(c, g, idx, k, a);
+  } else {
+#pragma unroll 1
+    for (uint32_t j = 0; j < (uint32_t)CHUNKS; ++j) {
+      compare_chunk<DT, N>(c, g, idx + j * N, k, a);
+      drop_front<ES * N>(c);
+      drop_front<ES * N>(g);
+    }
+  }
 }
 
 __device__ __forceinline__ uint64_t load_word_any(const uint8_t* p, uint32_t valid, uint32_t es) {
@@ -617,25 +718,27 @@ __device__ __forceinline__ uint32_t vec_diff(u32x4 c, u32x4 g) {
   return (c.x ^ g.x) | (c.y ^ g.y) | (c.z ^ g.z) | (c.w ^ g.w);
 }
 
-__device__ __forceinline__ void compare_tile(const uint8_t* cbase, const uint8_t* gbase, uint32_t len,
-                                             uint64_t word0, const ElemKind& k, uint32_t lane, Acc& a) {
-  const uint32_t epw = 8 / k.es;
-  if (((uintptr_t)cbase & 15) == 0) {
-    const u32x4* C = (const u32x4*)cbase;
-    const u32x4* G = (const u32x4*)gbase;
-    const uint32_t nvec = len >> 4;
-    uint64_t key = (word0 + 2ull * lane + 1) * kPhi;
-    uint32_t v = lane;
-    const uint32_t nfull = nvec / (64 * kUnroll);
-    for (uint32_t it = 0; it < nfull; ++it) {
-      u32x4 c[kUnroll], g[kUnroll];
+// The whole 16-byte vectors of an aligned tile: nvec vectors at C / G, vector v belongs to
+// lane v % 64.  key = checksum key of this lane's first word.  The last round may be short:
+// its missing vectors read as zeros on both sides and take no part in the checksum.
+template <int DT>
+__device__ __forceinline__ void compare_vectors(const u32x4* C, const u32x4* G, uint32_t nvec,
+                                                uint64_t key, const ElemKind& k, uint32_t lane, Acc& a) {
+  constexpr uint32_t EPV = 16 / Elem<DT>::size;  // elements per vector
+  constexpr uint32_t kRound = 64 * kUnroll;      // vectors per round of the wavefront
+  uint32_t v = lane;
+  const uint32_t nfull = nvec / kRound;
+  const uint32_t rounds = (nvec + kRound - 1) / kRound;
+  for (uint32_t it = 0; it < rounds; ++it) {
+    u32x4 c[kUnroll], g[kUnroll];
+    uint32_t diff = 0;
+    if (it < nfull) {
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) {
         c[u] = __builtin_nontemporal_load(C + v + 64 * u);
         g[u] = __builtin_nontemporal_load(G + v + 64 * u);
       }
       // Fast path: checksum every vector, gather one "something differs" flag.
-      uint32_t diff = 0;
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) {
         const uint64_t ku = key + (uint64_t)u * kVecKeyStep;
@@ -643,71 +746,70 @@ __device__ __forceinline__ void compare_tile(const uint8_t* cbase, const uint8_t
         a.cks += cks_term(c[u].z, c[u].w, ku + kPhi);
         diff |= vec_diff(c[u], g[u]);
       }
-      if (__builtin_amdgcn_ballot_w64(diff != 0) != 0) {
-        // Something differs: walk the vectors again, one code site for all of them.
-        static_assert(kUnroll == 4, "the selection below is written for four vectors");
-#pragma unroll 1
-        for (uint32_t u = 0; u < (uint32_t)kUnroll; ++u) {
-          const u32x4 cc = u == 0 ? c[0] : u == 1 ? c[1] : u == 2 ? c[2] : c[3];
-          const u32x4 gg = u == 0 ? g[0] : u == 1 ? g[1] : u == 2 ? g[2] : g[3];
-          bool grew = false;
-          if (vec_diff(cc, gg)) grew = differing_vec(cc, gg, (v + 64 * u) * (2 * epw), k, a);
-          refresh_gate_if(grew, a);
+    } else {
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        c[u] = u32x4{0, 0, 0, 0};
+        g[u] = u32x4{0, 0, 0, 0};
+        if (v + 64 * u < nvec) {
+          c[u] = __builtin_nontemporal_load(C + v + 64 * u);
+          g[u] = __builtin_nontemporal_load(G + v + 64 * u);
+          const uint64_t ku = key + (uint64_t)u * kVecKeyStep;
+          a.cks += cks_term(c[u].x, c[u].y, ku);
+          a.cks += cks_term(c[u].z, c[u].w, ku + kPhi);
         }
+        diff |= vec_diff(c[u], g[u]);
       }
-      v += 64 * kUnroll;
-      key += (uint64_t)kUnroll * kVecKeyStep;
     }
-    // Remaining whole vectors, same trip count for all lanes.
-    const uint32_t rest = nvec - nfull * 64 * kUnroll;
-    const uint32_t trips = (rest + 63) >> 6;
-    for (uint32_t it = 0; it < trips; ++it) {
-      u32x4 c = {0, 0, 0, 0}, g = {0, 0, 0, 0};
-      if (v < nvec) {
-        c = __builtin_nontemporal_load(C + v);
-        g = __builtin_nontemporal_load(G + v);
-        a.cks += cks_term(c.x, c.y, key);
-        a.cks += cks_term(c.z, c.w, key + kPhi);
+    if (__builtin_amdgcn_ballot_w64(diff != 0) != 0) {
+      // One code site for the four vectors (the kernel has to fit the instruction cache).
+#pragma unroll 1
+      for (uint32_t u = 0; u < (uint32_t)kUnroll; ++u) {
+        const u32x4 cc = c[u], gg = g[u];
+        if (__builtin_amdgcn_ballot_w64(vec_diff(cc, gg) != 0) != 0)
+          compare_vector<DT>(cc, gg, (v + 64 * u) * EPV, k, a);
       }
-      const bool dv = vec_diff(c, g) != 0;
-      if (__builtin_amdgcn_ballot_w64(dv) != 0) {
-        bool grew = false;
-        if (dv) grew = differing_vec(c, g, v * (2 * epw), k, a);
-        refresh_gate_if(grew, a);
-      }
-      v += 64;
-      key += kVecKeyStep;
     }
-    const uint32_t tail = len & 15;
-    const uint32_t tail_words = (tail + 7) >> 3;
-    if (tail_words) {  // uniform: only the last tile of a region whose size is not 16 k
-      bool grew = false;
-      if (lane < tail_words) {
-        const uint32_t at = (nvec << 4) + 8 * lane;
-        const uint32_t valid = (len - at) < 8 ? (len - at) : 8;
-        const uint64_t wc = load_word_any(cbase + at, valid, k.es);
-        const uint64_t wg = load_word_any(gbase + at, valid, k.es);
-        a.cks += cks_term((uint32_t)wc, (uint32_t)(wc >> 32), (word0 + 2ull * nvec + lane + 1) * kPhi);
-        grew = differing_word(wc, wg, valid / k.es, at / k.es, k, a);
-      }
-      refresh_gate_if(grew, a);
+    v += kRound;
+    key += (uint64_t)kUnroll * kVecKeyStep;
+  }
+}
+
+__device__ __forceinline__ void compare_tile(const uint8_t* cbase, const uint8_t* gbase, uint32_t len,
+                                             uint64_t word0, const ElemKind& k, uint32_t lane, Acc& a) {
+  const uint32_t epw = 8 / k.es;
+  uint32_t first_word = 0;  // where the word-by-word loop below starts
+  if (((uintptr_t)cbase & 15) == 0) {
+    const u32x4* C = (const u32x4*)cbase;
+    const u32x4* G = (const u32x4*)gbase;
+    const uint32_t nvec = len >> 4;
+    const uint64_t key = (word0 + 2ull * lane + 1) * kPhi;
+    switch (k.dtype) {  // uniform across the wavefront
+      case R3_U8: compare_vectors<R3_U8>(C, G, nvec, key, k, lane, a); break;
+      case R3_F32: compare_vectors<R3_F32>(C, G, nvec, key, k, lane, a); break;
+      case R3_F64: compare_vectors<R3_F64>(C, G, nvec, key, k, lane, a); break;
+      case R3_I32: compare_vectors<R3_I32>(C, G, nvec, key, k, lane, a); break;
+      case R3_BF16: compare_vectors<R3_BF16>(C, G, nvec, key, k, lane, a); break;
+      default: compare_vectors<R3_F16>(C, G, nvec, key, k, lane, a); break;
     }
-  } else {
-    const uint32_t nwords = (len + 7) >> 3;
-    const uint32_t trips = (nwords + 63) >> 6;
-    uint32_t j = lane;
-    for (uint32_t it = 0; it < trips; ++it, j += 64) {
-      bool grew = false;
-      if (j < nwords) {
-        const uint32_t at = 8 * j;
-        const uint32_t valid = (len - at) < 8 ? (len - at) : 8;
-        const uint64_t wc = load_word_any(cbase + at, valid, k.es);
-        const uint64_t wg = load_word_any(gbase + at, valid, k.es);
-        a.cks += cks_term((uint32_t)wc, (uint32_t)(wc >> 32), (word0 + j + 1) * kPhi);
-        grew = differing_word(wc, wg, valid / k.es, j * epw, k, a);
-      }
-      refresh_gate_if(grew, a);
+    first_word = 2 * nvec;  // what is left: fewer than 16 bytes at the end of a region
+  }
+  // Word by word: the whole tile when the region does not start on a 16-byte boundary,
+  // otherwise only the last one or two words of a region whose size is not a multiple of 16.
+  const uint32_t nwords = (len + 7) >> 3;
+  const uint32_t trips = (nwords - first_word + 63) >> 6;
+  uint32_t j = first_word + lane;
+  for (uint32_t it = 0; it < trips; ++it, j += 64) {
+    bool grew = false;
+    if (j < nwords) {
+      const uint32_t at = 8 * j;
+      const uint32_t valid = (len - at) < 8 ? (len - at) : 8;
+      const uint64_t wc = load_word_any(cbase + at, valid, k.es);
+      const uint64_t wg = load_word_any(gbase + at, valid, k.es);
+      a.cks += cks_term((uint32_t)wc, (uint32_t)(wc >> 32), (word0 + j + 1) * kPhi);
+      grew = differing_word(wc, wg, valid / k.es, j * epw, k, a);
     }
+    refresh_top_if(grew, a);
   }
 }
 
@@ -729,7 +831,7 @@ __device__ __forceinline__ void compare_tile_to_partial(const TileView& tv, cons
   a.first = 0xFFFFFFFFu;
   a.max_abs = 0.0;
   a.max_rel = 0.0;
-  a.gate = 0.0;
+  a.top = 0.0;
   a.cks = 0;
   compare_tile(live + at, golden + at, tv.len, word0, k, lane, a);
   // Fold the wavefront.  A tile in which no lane saw a differing element (the usual case)

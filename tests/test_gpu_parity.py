@@ -568,3 +568,113 @@ def test_compare_every_binary16_pattern(env, oracle):
     exp_res, _ = oracle.compare(oracle.make_table(rows1), p.view(np.uint8), q.view(np.uint8))
     res, _ = run_compare(r3, ctx, torch, rows1, dev(torch, p.view(np.uint8)), dev(torch, q.view(np.uint8)), 2 * m)
     assert_results_equal(res, exp_res, "single binary16 elements")
+
+
+# ----------------------------------------------------------------------------------------
+# states that differ from the recorded one in (almost) every element
+# ----------------------------------------------------------------------------------------
+def _dense_case(rng, dt, n_el):
+    """Golden values of moderate size, live = golden moved by a few pattern steps in every element,
+    then special cases planted all over: zeros on either side, NaN and infinity against finite values
+    and against themselves, many elements with one and the same error ratio, a few outliers late in
+    the region.  Returns (golden bytes, live bytes)."""
+    es = ri.ELEM_SIZE[dt]
+    if dt == ri.U8:
+        g = rng.integers(0, 256, n_el, dtype=np.uint8)
+        c = (g.astype(np.int32) + rng.integers(-2, 3, n_el)).astype(np.uint8)
+    elif dt == ri.I32:
+        g = rng.integers(-2**31, 2**31, n_el, dtype=np.int64).astype(np.int32)
+        c = (g.astype(np.int64) + rng.integers(-3, 4, n_el)).astype(np.int32)
+    else:
+        x = rng.standard_normal(n_el) * np.exp(rng.uniform(-3, 3, n_el))
+        if dt == ri.F64:
+            g = x.astype("<f8")
+            ib = g.view(np.int64)
+        elif dt == ri.F32:
+            g = x.astype("<f4")
+            ib = g.view(np.int32)
+        elif dt == ri.F16:
+            g = x.astype("<f2")
+            ib = g.view(np.int16)
+        else:
+            g = ri.f32_to_bf16_bits(x.astype("<f4")).view(np.int16).copy()
+            ib = g
+        c = (ib.astype(np.int64) + rng.integers(-2, 3, n_el)).astype(ib.dtype)
+    g = np.ascontiguousarray(g).view(np.uint8).reshape(n_el, es).copy()
+    c = np.ascontiguousarray(c).view(np.uint8).reshape(n_el, es).copy()
+
+    def pat(v):
+        return np.frombuffer(int(v).to_bytes(es, "little"), dtype=np.uint8)
+    is_float = dt in (ri.F32, ri.F64, ri.BF16, ri.F16)
+    if is_float:
+        one = {ri.F32: 0x3F800000, ri.F64: 0x3FF0000000000000, ri.BF16: 0x3F80, ri.F16: 0x3C00}[dt]
+        two = {ri.F32: 0x40000000, ri.F64: 0x4000000000000000, ri.BF16: 0x4000, ri.F16: 0x4000}[dt]
+        inf = {ri.F32: 0x7F800000, ri.F64: 0x7FF0000000000000, ri.BF16: 0x7F80, ri.F16: 0x7C00}[dt]
+        nan = inf | 1
+        big = {ri.F32: 0x7F000000, ri.F64: 0x7FE0000000000000, ri.BF16: 0x7F00, ri.F16: 0x7800}[dt]
+        sign = 1 << (8 * es - 1)
+        specials = [(0, 0), (sign, 0), (0, sign), (one, 0), (0, one), (nan, 0), (inf, 0), (0, nan), (0, inf),
+                    (nan, nan), (inf, inf), (inf, inf | sign), (nan, one), (one, nan), (inf, one), (one, inf),
+                    (big, big | sign), (1, 0), (0, 1), (1, 2), (two, one), (one, two)]
+    else:
+        specials = [(0, 0), (1, 0), (0, 1), (3, 1), (1, 3), (2, 1), (200, 100), (100, 200), (4, 2), (6, 3)]
+        if dt == ri.I32:
+            specials += [(0x7FFFFFFF, 0x80000000), (0x80000000, 0x7FFFFFFF), (0xFFFFFFFF, 1), (1, 0xFFFFFFFF)]
+    where = rng.choice(n_el, size=min(n_el // 2, 40 * len(specials)), replace=False)
+    for j, q in enumerate(where):
+        cv, gv = specials[j % len(specials)]
+        c[q], g[q] = pat(cv), pat(gv)
+    # a run of equal error ratios (live = 2 * golden exactly where that is representable)
+    lo = n_el // 3
+    for q in range(lo, min(n_el, lo + 300)):
+        if is_float:
+            c[q], g[q] = pat(two), pat(one)
+        else:
+            c[q], g[q] = pat(2), pat(1)
+    return g.reshape(-1), c.reshape(-1)
+
+
+@pytest.mark.parametrize("mode", [ri.TOL, ri.BITWISE])
+def test_compare_dense_differences(env, oracle, mode):
+    """Every element differs (what a numerically equivalent rewrite looks like), every element type,
+    several tiles and a ragged tail per region, regions at 16-byte aligned and at odd offsets."""
+    r3, ctx, torch = env
+    rng = np.random.default_rng(977 + mode)
+    rows, parts, at = [], [], 0
+    for rep, (n_bytes, odd) in enumerate([(150000, False), (41000, True), (4096 * 3, False), (120, False)]):
+        for dt in (ri.F32, ri.F64, ri.BF16, ri.F16, ri.I32, ri.U8):
+            es = ri.ELEM_SIZE[dt]
+            n_el = n_bytes // es
+            g, c = _dense_case(rng, dt, n_el)
+            at = (at + 255) // 256 * 256 + (es if odd else 0)
+            rtol, atol = {ri.F32: (1e-6, 1e-8), ri.F64: (1e-15, 0.0), ri.BF16: (1e-2, 1e-3), ri.F16: (1e-3, 1e-4),
+                          ri.I32: (1e-9, 1.0), ri.U8: (1e-2, 1.0)}[dt]
+            rows.append((at, n_el * es, dt, mode, rtol, atol))
+            parts.append((at, g, c))
+            at += n_el * es
+    arena = (at + 255) // 256 * 256
+    gold = rng.integers(0, 256, arena, dtype=np.uint8)
+    live = gold.copy()
+    for off, g, c in parts:
+        gold[off:off + g.size] = g
+        live[off:off + c.size] = c
+    print("case dense differences mode", mode, "regions", len(rows), "bytes", arena, flush=True)
+    exp_res, exp_sum = oracle.compare(oracle.make_table(rows), live, gold)
+    res, summ = run_compare(r3, ctx, torch, rows, dev(torch, live), dev(torch, gold), arena)
+    assert_results_equal(res, exp_res, "dense differences")
+    assert summ.tobytes() == exp_sum.tobytes()
+    assert int(exp_sum[0]["total_mismatch"]) > 0
+    # the same data without the non-finite values: errors stay finite and the maxima are real quotients
+    for (off, nb, dt, *_), (_, g, c) in zip(rows, parts):
+        es = ri.ELEM_SIZE[dt]
+        if dt in (ri.F32, ri.F64, ri.BF16, ri.F16):
+            top = {ri.F32: 0x7F, ri.F64: 0x7F, ri.BF16: 0x7F, ri.F16: 0x7C}[dt]
+            for buf in (gold, live):
+                hi = buf[off + es - 1:off + nb:es]
+                bad = (hi & 0x7F) >= (top if dt != ri.F16 else 0x78)
+                hi[bad] &= 0xBF
+    exp_res, exp_sum = oracle.compare(oracle.make_table(rows), live, gold)
+    res, summ = run_compare(r3, ctx, torch, rows, dev(torch, live), dev(torch, gold), arena)
+    assert_results_equal(res, exp_res, "dense differences, finite")
+    assert summ.tobytes() == exp_sum.tobytes()
+    assert np.isfinite(exp_res["max_rel_err"]).all()
