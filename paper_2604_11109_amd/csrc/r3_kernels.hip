@@ -380,12 +380,15 @@ __global__ __launch_bounds__(BLOCK) void checksum_finalize_kernel(TableDev t, ui
 // Fused compare + checksum
 // =======================================================================================
 struct Acc {
-  uint32_t count;  // mismatches in this lane
-  uint32_t first;  // smallest mismatching element index inside the tile, ~0u if none
+  uint32_t count;   // mismatches counted by this lane (careful paths, tails)
+  uint32_t first;   // smallest mismatching element index this lane has seen, ~0u if none
+  uint32_t wcount;  // mismatches counted for the whole wavefront at once (uniform, scalar)
+  uint32_t wfirst;  // smallest mismatching element index found that way (uniform), ~0u if none
   double max_abs;
   double max_rel;
   double top;      // a lower bound of the tile's final max_rel: this lane's own maximum or the
                    // wavefront's at its last exchange, whichever is larger
+  double tq;       // top cut down to so few significant bits that tq * |G| is exact (set_top)
   uint64_t cks;
 };
 
@@ -435,13 +438,24 @@ __device__ __forceinline__ bool may_raise_max_rel(double d, double aG, double to
   return !(below | (d == 0.0));
 }
 
-// The relative error of one element whose quotient may raise the maximum.  Returns true when
-// this lane's max_rel grew.
-__device__ __forceinline__ bool raise_max_rel(double d, double G, double aG, Acc& a) {
-  const double r = (G == 0.0) ? 0.0 : d / aG;
+// A new lower bound of max_rel.  tq keeps the leading 21 significant bits of it (the low 32
+// mantissa bits cleared), so that its product with any |G| of at most 32 significant bits -
+// every element type but binary64 - is exact.  An infinite top (a NaN or infinity mismatch
+// was seen, nothing can raise max_rel any more) gives a large finite tq, which lets finite
+// errors pass the quick test.
+__device__ __forceinline__ void set_top(Acc& a, double top) {
+  a.top = top;
+  const double cut = bits_d(dbits(top) & ~0xFFFFFFFFull);
+  a.tq = top < kInf ? cut : 0x1p500;
+}
+
+// The relative error of one element whose quotient may raise the maximum (aG == 0 means
+// G == 0: no relative error by rule).  Returns true when this lane's max_rel grew.
+__device__ __forceinline__ bool raise_max_rel(double d, double aG, Acc& a) {
+  const double r = (aG == 0.0) ? 0.0 : d / aG;
   if (r > a.max_rel) {
     a.max_rel = r;
-    a.top = r > a.top ? r : a.top;
+    if (r > a.top) set_top(a, r);
     return true;
   }
   return false;
@@ -459,7 +473,7 @@ __device__ __forceinline__ bool differing_elem(uint64_t cb, uint64_t gb, uint32_
     mis = true;
     if (!(a.max_rel == kInf)) {
       a.max_rel = kInf;
-      a.top = kInf;
+      set_top(a, kInf);
       grew = true;
     }
   } else {
@@ -471,7 +485,7 @@ __device__ __forceinline__ bool differing_elem(uint64_t cb, uint64_t gb, uint32_
     } else {
       mis = true;
     }
-    if (may_raise_max_rel(d, aG, a.top)) grew = raise_max_rel(d, G, aG, a);
+    if (may_raise_max_rel(d, aG, a.top)) grew = raise_max_rel(d, aG, a);
   }
   a.max_abs = d > a.max_abs ? d : a.max_abs;
   a.count += mis ? 1u : 0u;
@@ -573,7 +587,7 @@ __device__ __forceinline__ bool careful_elem(uint64_t cb, uint64_t gb, uint32_t 
   } else {
     mis = differ;
   }
-  if (!rel_done && may_raise_max_rel(d, aG, a.top)) grew |= raise_max_rel(d, G, aG, a);
+  if (!rel_done && may_raise_max_rel(d, aG, a.top)) grew |= raise_max_rel(d, aG, a);
   a.max_abs = d > a.max_abs ? d : a.max_abs;
   a.count += mis ? 1u : 0u;
   const uint32_t cand = mis ? idx : 0xFFFFFFFFu;
@@ -584,7 +598,7 @@ __device__ __forceinline__ bool careful_elem(uint64_t cb, uint64_t gb, uint32_t 
 // The wavefront shares its largest max_rel.  Called by all lanes (uniform control flow).
 __device__ __forceinline__ void refresh_top(Acc& a) {
   const double m = bits_d(dpp_max(dbits(a.max_rel)));
-  a.top = m > a.top ? m : a.top;
+  if (m > a.top) set_top(a, m);
 }
 __device__ __forceinline__ void refresh_top_if(bool grew, Acc& a) {
   if (__builtin_amdgcn_ballot_w64(grew) != 0) refresh_top(a);
@@ -623,82 +637,136 @@ __device__ __forceinline__ uint64_t pop_elem(u32x4& v) {
   return bits;
 }
 
-// The first N elements of the vectors c and g; idx = tile index of the first.  All lanes take
-// part (uniform control flow).
+// The quick form of may_raise_max_rel for element types of at most 32 significant bits:
+// ph = tq * |G| is exact while it is a normal number or zero, so d <= ph proves
+// d/|G| <= tq <= top (and d == 0 when ph == 0).
+__device__ __forceinline__ bool may_raise_quick(double t, double aG, double tq) {
+  const double ph = tq * aG;
+  const bool exact = __builtin_isnormal(ph) | (ph == 0.0);
+  return !((__builtin_fabs(t) <= ph) & exact);
+}
+
+// max(m, |t|) for a finite t in one instruction (a plain fmax costs a second one that
+// quiets signalling NaNs, which cannot occur where this is used).
+__device__ __forceinline__ double max_with_abs(double m, double t) {
+  double r;
+  asm("v_max_f64 %0, %1, |%2|" : "=v"(r) : "v"(m), "v"(t));
+  return r;
+}
+
+// The first N elements of the vectors c and g.  idx0 = tile index of the first of them in
+// lane 0; lane L holds the elements EPV * L further on.  All lanes take part (uniform
+// control flow).
 template <int DT, int N>
-__device__ __forceinline__ void compare_chunk(const u32x4& c, const u32x4& g, uint32_t idx,
+__device__ __forceinline__ void compare_chunk(const u32x4& c, const u32x4& g, uint32_t idx0,
                                               const ElemKind& k, Acc& a) {
+  constexpr bool kQuick = Elem<DT>::size < 8;
+  constexpr uint32_t EPV = 16 / Elem<DT>::size;
   uint64_t cb[N], gb[N];
-  double aG[N], d[N];
-  bool need = false;
+  double aG[N], t[N];  // |G| and the signed difference C - G
+  bool any_flag = false;
+  bool flag[N];
 #pragma unroll
   for (int e = 0; e < N; ++e) {
     cb[e] = elem_bits<DT>(c, e);
     gb[e] = elem_bits<DT>(g, e);
     const double C = to_f64_t<DT>(cb[e]), G = to_f64_t<DT>(gb[e]);
     aG[e] = __builtin_fabs(G);
-    d[e] = __builtin_fabs(C - G);
-    need |= may_raise_max_rel(d[e], aG[e], a.top);
+    t[e] = C - G;
+    flag[e] = kQuick ? may_raise_quick(t[e], aG[e], a.tq)
+                     : may_raise_max_rel(__builtin_fabs(t[e]), aG[e], a.top);
+    any_flag |= flag[e];
   }
-  if (__builtin_amdgcn_ballot_w64(need) != 0) {
-    // The careful path: element by element under the full rules, one copy of the code (it
-    // runs while a tile's max_rel is still rising, and for NaN / infinity).
-    u32x4 cw = c, gw = g;
-    bool grew = false;
-#pragma unroll 1
-    for (uint32_t e = 0; e < (uint32_t)N; ++e) {
-      const uint64_t ce = pop_elem<DT>(cw), ge = pop_elem<DT>(gw);
-      grew |= careful_elem<DT>(ce, ge, idx + e, k, a);
+  // Per lane, which of its elements may raise max_rel (or are NaN / infinite).  Usually none.
+  uint32_t pend = 0;
+  if (__builtin_amdgcn_ballot_w64(any_flag) != 0) {
+    bool odd = false;  // an error that is NaN or infinite: the plain predicate does not apply
+#pragma unroll
+    for (int e = 0; e < N; ++e) {
+      const double d = __builtin_fabs(t[e]);
+      if (kQuick) flag[e] = flag[e] & may_raise_max_rel(d, aG[e], a.top);
+      odd |= flag[e] & !(d < kInf);
+      pend |= flag[e] ? (1u << e) : 0u;
     }
-    refresh_top_if(grew, a);
-    return;
+    if (__builtin_amdgcn_ballot_w64(odd) != 0) {
+      // The careful path: element by element under the full rules, one copy of the code.
+      u32x4 cw = c, gw = g;
+      const uint32_t idx = idx0 + lane_id() * EPV;
+      bool grew = false;
+#pragma unroll 1
+      for (uint32_t e = 0; e < (uint32_t)N; ++e) {
+        const uint64_t ce = pop_elem<DT>(cw), ge = pop_elem<DT>(gw);
+        grew |= careful_elem<DT>(ce, ge, idx + e, k, a);
+      }
+      refresh_top_if(grew, a);
+      return;
+    }
   }
-  // Every d here is finite (an infinite or NaN error never passes the test above), so both
-  // inputs are finite and the plain predicate applies.
-  bool mis[N];
+  // Every error here is finite, so both inputs are finite and the plain predicate applies.
+  // Mismatches are counted for the whole wavefront at once from the lane masks.
+  uint64_t m[N];
   if (k.tol) {
 #pragma unroll
     for (int e = 0; e < N; ++e) {
-      const double t = k.rtol * aG[e];
-      const double thr = k.atol + t;
-      mis[e] = d[e] > thr;
+      const double rt = k.rtol * aG[e];
+      const double thr = k.atol + rt;
+      m[e] = __builtin_amdgcn_ballot_w64(__builtin_fabs(t[e]) > thr);
     }
   } else {
 #pragma unroll
-    for (int e = 0; e < N; ++e) mis[e] = cb[e] != gb[e];
+    for (int e = 0; e < N; ++e) m[e] = __builtin_amdgcn_ballot_w64(cb[e] != gb[e]);
   }
-  bool any = false;
+  uint64_t any = 0;
 #pragma unroll
   for (int e = 0; e < N; ++e) {
-    any |= mis[e];
-    a.max_abs = __builtin_fmax(a.max_abs, d[e]);
+    any |= m[e];
+    a.wcount += (uint32_t)__builtin_popcountll(m[e]);
+    a.max_abs = max_with_abs(a.max_abs, t[e]);
   }
-  // a lane's indices only grow, so its first mismatch is the one that ends first == ~0u
-  if (__builtin_amdgcn_ballot_w64(any & (a.first == 0xFFFFFFFFu)) != 0) {
-    if (any & (a.first == 0xFFFFFFFFu)) {
-      uint32_t f = 0xFFFFFFFFu;
+  // The smallest index among them: the lowest lane with a mismatch, its lowest element.  Only
+  // looked for while this chunk can still hold a smaller index than the one known.
+  if (any != 0 && idx0 < a.wfirst) {
+    const uint32_t lane = (uint32_t)__builtin_ctzll(any);
+    uint32_t e0 = N - 1;
 #pragma unroll
-      for (int e = N - 1; e >= 0; --e) f = mis[e] ? idx + e : f;
-      a.first = f;
-    }
+    for (int e = N - 2; e >= 0; --e) e0 = ((m[e] >> lane) & 1) ? (uint32_t)e : e0;
+    const uint32_t cand = idx0 + lane * EPV + e0;
+    a.wfirst = cand < a.wfirst ? cand : a.wfirst;
   }
+  // The quotients that may raise max_rel, one per lane and round (usually one round).
+  if (__builtin_amdgcn_ballot_w64(pend != 0) != 0) {
+    bool grew = false;
+    do {
+      if (pend != 0) {
+        const uint32_t e = (uint32_t)__builtin_ctz(pend);
+        pend &= pend - 1;
+        double tt = t[0], gg = aG[0];
 #pragma unroll
-  for (int e = 0; e < N; ++e) a.count += mis[e] ? 1u : 0u;
+        for (int j = 1; j < N; ++j) {
+          tt = e == (uint32_t)j ? t[j] : tt;
+          gg = e == (uint32_t)j ? aG[j] : gg;
+        }
+        const double dd = __builtin_fabs(tt);
+        if (may_raise_max_rel(dd, gg, a.top)) grew |= raise_max_rel(dd, gg, a);
+      }
+    } while (__builtin_amdgcn_ballot_w64(pend != 0) != 0);
+    refresh_top_if(grew, a);
+  }
 }
 
-// One whole vector per lane; idx = tile index of the vector's first element.  The chunks of
-// a vector go through one copy of the code.
+// One whole vector per lane; idx0 = tile index of the first element of lane 0's vector.  The
+// chunks of a vector go through one copy of the code.
 template <int DT>
-__device__ __forceinline__ void compare_vector(u32x4 c, u32x4 g, uint32_t idx, const ElemKind& k, Acc& a) {
+__device__ __forceinline__ void compare_vector(u32x4 c, u32x4 g, uint32_t idx0, const ElemKind& k, Acc& a) {
   constexpr int ES = Elem<DT>::size;
   constexpr int N = ES == 8 ? 2 : 4;         // elements per chunk
   constexpr int CHUNKS = 16 / (ES * N);      // 1, 1, 2, 4 for 8-, 4-, 2-, 1-byte elements
   if constexpr (CHUNKS == 1) {
-    compare_chunk<DT, N>(c, g, idx, k, a);
+    compare_chunk<DT, N>(c, g, idx0, k, a);
   } else {
 #pragma unroll 1
     for (uint32_t j = 0; j < (uint32_t)CHUNKS; ++j) {
-      compare_chunk<DT, N>(c, g, idx + j * N, k, a);
+      compare_chunk<DT, N>(c, g, idx0 + j * N, k, a);
       drop_front<ES * N>(c);
       drop_front<ES * N>(g);
     }
@@ -727,6 +795,7 @@ __device__ __forceinline__ void compare_vectors(const u32x4* C, const u32x4* G, 
   constexpr uint32_t EPV = 16 / Elem<DT>::size;  // elements per vector
   constexpr uint32_t kRound = 64 * kUnroll;      // vectors per round of the wavefront
   uint32_t v = lane;
+  uint32_t v0 = 0;  // the vector lane 0 starts this round with (uniform)
   const uint32_t nfull = nvec / kRound;
   const uint32_t rounds = (nvec + kRound - 1) / kRound;
   for (uint32_t it = 0; it < rounds; ++it) {
@@ -767,10 +836,11 @@ __device__ __forceinline__ void compare_vectors(const u32x4* C, const u32x4* G, 
       for (uint32_t u = 0; u < (uint32_t)kUnroll; ++u) {
         const u32x4 cc = c[u], gg = g[u];
         if (__builtin_amdgcn_ballot_w64(vec_diff(cc, gg) != 0) != 0)
-          compare_vector<DT>(cc, gg, (v + 64 * u) * EPV, k, a);
+          compare_vector<DT>(cc, gg, (v0 + 64 * u) * EPV, k, a);
       }
     }
     v += kRound;
+    v0 += kRound;
     key += (uint64_t)kUnroll * kVecKeyStep;
   }
 }
@@ -829,9 +899,12 @@ __device__ __forceinline__ void compare_tile_to_partial(const TileView& tv, cons
   Acc a;
   a.count = 0;
   a.first = 0xFFFFFFFFu;
+  a.wcount = 0;
+  a.wfirst = 0xFFFFFFFFu;
   a.max_abs = 0.0;
   a.max_rel = 0.0;
   a.top = 0.0;
+  a.tq = 0.0;
   a.cks = 0;
   compare_tile(live + at, golden + at, tv.len, word0, k, lane, a);
   // Fold the wavefront.  A tile in which no lane saw a differing element (the usual case)
@@ -839,14 +912,16 @@ __device__ __forceinline__ void compare_tile_to_partial(const TileView& tv, cons
   const uint64_t cks = dpp_sum(a.cks);
   const bool touched = a.count != 0 || a.first != 0xFFFFFFFFu || dbits(a.max_abs) != 0 ||
                        dbits(a.max_rel) != 0;
-  uint64_t count = 0, first_elem = R3_NO_INDEX, max_abs = 0, max_rel = 0;
+  uint64_t count = a.wcount, first_elem = R3_NO_INDEX, max_abs = 0, max_rel = 0;
+  uint32_t first = a.wfirst;
   if (__builtin_amdgcn_ballot_w64(touched) != 0) {
-    count = dpp_sum(a.count);
-    const uint32_t first = dpp_min(a.first);
+    count += dpp_sum(a.count);
+    const uint32_t lane_first = dpp_min(a.first);
+    first = lane_first < first ? lane_first : first;
     max_abs = dpp_max(dbits(a.max_abs));
     max_rel = dpp_max(dbits(a.max_rel));
-    if (first != 0xFFFFFFFFu) first_elem = tv.rel_start / k.es + first;
   }
+  if (first != 0xFFFFFFFFu) first_elem = tv.rel_start / k.es + first;
   uint64_t* out = (uint64_t*)dst;
   if (lane < 5) {
     const uint64_t val = lane == 0 ? count : lane == 1 ? first_elem : lane == 2 ? max_abs
