@@ -379,17 +379,24 @@ __global__ __launch_bounds__(BLOCK) void checksum_finalize_kernel(TableDev t, ui
 // =======================================================================================
 // Fused compare + checksum
 // =======================================================================================
+// What a wavefront knows about its tile.  Everything but max_abs and the checksum is kept
+// for the wavefront as a whole (uniform values, scalar registers): the common path updates
+// them from lane masks, the rare paths work on a LaneAcc of their own and fold it in when
+// they are done.
 struct Acc {
-  uint32_t count;   // mismatches counted by this lane (careful paths, tails)
-  uint32_t first;   // smallest mismatching element index this lane has seen, ~0u if none
-  uint32_t wcount;  // mismatches counted for the whole wavefront at once (uniform, scalar)
-  uint32_t wfirst;  // smallest mismatching element index found that way (uniform), ~0u if none
-  double max_abs;
+  uint32_t wcount;    // mismatches so far
+  uint32_t wfirst;    // smallest mismatching element index inside the tile, ~0u if none
+  uint64_t top_bits;  // bit pattern of top = the largest relative error so far (the tile's max_rel)
+  uint64_t tq_bits;   // bit pattern of tq = top cut down so that tq * |G| is exact (set_top)
+  double max_abs;     // per lane
+  uint64_t cks;       // per lane
+};
+
+// What one lane gathers inside a rare path.
+struct LaneAcc {
+  uint32_t count;
+  uint32_t first;  // ~0u if none
   double max_rel;
-  double top;      // a lower bound of the tile's final max_rel: this lane's own maximum or the
-                   // wavefront's at its last exchange, whichever is larger
-  double tq;       // top cut down to so few significant bits that tq * |G| is exact (set_top)
-  uint64_t cks;
 };
 
 // How the elements of the region at hand are read (wavefront-uniform).
@@ -438,90 +445,109 @@ __device__ __forceinline__ bool may_raise_max_rel(double d, double aG, double to
   return !(below | (d == 0.0));
 }
 
-// A new lower bound of max_rel.  tq keeps the leading 21 significant bits of it (the low 32
-// mantissa bits cleared), so that its product with any |G| of at most 32 significant bits -
-// every element type but binary64 - is exact.  An infinite top (a NaN or infinity mismatch
-// was seen, nothing can raise max_rel any more) gives a large finite tq, which lets finite
-// errors pass the quick test.
-__device__ __forceinline__ void set_top(Acc& a, double top) {
-  a.top = top;
-  const double cut = bits_d(dbits(top) & ~0xFFFFFFFFull);
-  a.tq = top < kInf ? cut : 0x1p500;
+// The quick form for element types of at most 32 significant bits, t = C - G: tq keeps the
+// leading 21 significant bits of top, so ph = tq * |G| is exact while it is a normal number
+// or zero, and |t| <= ph proves |t|/|G| <= tq <= top (and t == 0 when ph == 0).
+__device__ __forceinline__ bool may_raise_quick(double t, double aG, double tq) {
+  const double ph = tq * aG;
+  const bool exact = __builtin_isnormal(ph) | (ph == 0.0);
+  return !((__builtin_fabs(t) <= ph) & exact);
+}
+
+// A larger top for the wavefront (m is uniform).  An infinite top (a NaN or infinity
+// mismatch was seen, nothing can raise max_rel any more) gets a large finite tq, which lets
+// finite errors pass the quick test.
+__device__ __forceinline__ void raise_top(Acc& a, double m) {
+  if (m > bits_d(a.top_bits)) {
+    const uint64_t mb = dbits(m);
+    a.top_bits = sgpr(mb);
+    const uint64_t cut = m < kInf ? (mb & ~0xFFFFFFFFull) : dbits(0x1p500);
+    a.tq_bits = sgpr(cut);
+  }
+}
+
+// Fold what the lanes gathered in a rare path into the wavefront's state.  Called by all
+// lanes (uniform control flow).
+__device__ __forceinline__ void fold_lanes(Acc& a, const LaneAcc& l) {
+  if (__builtin_amdgcn_ballot_w64(l.count != 0) != 0) {
+    a.wcount += dpp_sum(l.count);
+    const uint32_t f = dpp_min(l.first);
+    a.wfirst = f < a.wfirst ? f : a.wfirst;
+  }
+  if (__builtin_amdgcn_ballot_w64(l.max_rel > bits_d(a.top_bits)) != 0)
+    raise_top(a, bits_d(dpp_max(dbits(l.max_rel))));
 }
 
 // The relative error of one element whose quotient may raise the maximum (aG == 0 means
-// G == 0: no relative error by rule).  Returns true when this lane's max_rel grew.
-__device__ __forceinline__ bool raise_max_rel(double d, double aG, Acc& a) {
+// G == 0: no relative error by rule).
+__device__ __forceinline__ void raise_max_rel(double d, double aG, LaneAcc& l) {
   const double r = (aG == 0.0) ? 0.0 : d / aG;
-  if (r > a.max_rel) {
-    a.max_rel = r;
-    if (r > a.top) set_top(a, r);
-    return true;
-  }
-  return false;
+  l.max_rel = r > l.max_rel ? r : l.max_rel;
 }
 
-// One element whose bit patterns differ (tails and regions that are not 16-byte aligned).
-__device__ __forceinline__ bool differing_elem(uint64_t cb, uint64_t gb, uint32_t idx,
-                                               const ElemKind& k, Acc& a) {
-  const double C = to_f64(cb, k.dtype), G = to_f64(gb, k.dtype);
-  bool grew = false, mis;
-  double d;
-  const double aC = __builtin_fabs(C), aG = __builtin_fabs(G);
-  if (k.is_float && !(aC < kInf && aG < kInf)) {  // NaN or infinity on either side
-    d = kInf;
-    mis = true;
-    if (!(a.max_rel == kInf)) {
-      a.max_rel = kInf;
-      set_top(a, kInf);
-      grew = true;
+// The larger of the wavefront's top and what this lane has found since.
+__device__ __forceinline__ double lane_top(const Acc& a, const LaneAcc& l) {
+  const double top = bits_d(a.top_bits);
+  return l.max_rel > top ? l.max_rel : top;
+}
+
+// One element whose bit patterns differ, under the full rules (tails, regions that are not
+// 16-byte aligned, and the careful path of the vector code, which also passes equal ones).
+__device__ __forceinline__ void full_rules(bool differ, double C, double G, bool is_float, uint32_t idx,
+                                           const ElemKind& k, Acc& a, LaneAcc& l) {
+  const double aG = __builtin_fabs(G);
+  double d = __builtin_fabs(C - G);
+  bool forced = false, rel_done = false;
+  if (!(d < kInf)) {  // NaN or +Inf: equal non-finite patterns, a non-finite input, fp64 overflow
+    if (!differ) {
+      d = 0.0;
+    } else if (is_float && !(__builtin_fabs(C) < kInf && aG < kInf)) {
+      d = kInf;
+      forced = true;
+      rel_done = true;
+      l.max_rel = kInf;
     }
-  } else {
-    d = __builtin_fabs(C - G);
-    if (k.tol) {
-      const double t = k.rtol * aG;
-      const double thr = k.atol + t;
-      mis = d > thr;
-    } else {
-      mis = true;
-    }
-    if (may_raise_max_rel(d, aG, a.top)) grew = raise_max_rel(d, aG, a);
   }
+  bool mis;
+  if (k.tol) {
+    const double t = k.rtol * aG;
+    const double thr = k.atol + t;
+    mis = forced || d > thr;
+  } else {
+    mis = differ;
+  }
+  if (!rel_done && may_raise_max_rel(d, aG, lane_top(a, l))) raise_max_rel(d, aG, l);
   a.max_abs = d > a.max_abs ? d : a.max_abs;
-  a.count += mis ? 1u : 0u;
+  l.count += mis ? 1u : 0u;
   const uint32_t cand = mis ? idx : 0xFFFFFFFFu;
-  a.first = cand < a.first ? cand : a.first;
-  return grew;
+  l.first = cand < l.first ? cand : l.first;
 }
 
 // One 64-bit word of live (wc) and golden (wg) data holding `nvalid` elements; idx = tile
 // index of its first element.  The element loop is deliberately not unrolled: this path only
 // serves tails and unaligned regions.
-__device__ __forceinline__ bool differing_word(uint64_t wc, uint64_t wg, uint32_t nvalid,
-                                               uint32_t idx, const ElemKind& k, Acc& a) {
-  if (wc == wg) return false;
-  if (k.es == 8) return differing_elem(wc, wg, idx, k, a);
-  bool grew = false;
+__device__ __forceinline__ void differing_word(uint64_t wc, uint64_t wg, uint32_t nvalid, uint32_t idx,
+                                               const ElemKind& k, Acc& a, LaneAcc& l) {
+  if (wc == wg) return;
   const uint32_t bits = 8 * k.es;
-  const uint64_t mask = (1ull << bits) - 1;
+  const uint64_t mask = k.es == 8 ? ~0ull : (1ull << bits) - 1;
 #pragma unroll 1
   for (uint32_t e = 0; e < nvalid; ++e) {
     const uint64_t cb = wc & mask, gb = wg & mask;
-    if (cb != gb) grew |= differing_elem(cb, gb, idx + e, k, a);
-    wc >>= bits;
-    wg >>= bits;
+    if (cb != gb) full_rules(true, to_f64(cb, k.dtype), to_f64(gb, k.dtype), k.is_float, idx + e, k, a, l);
+    wc = k.es == 8 ? 0 : wc >> bits;
+    wg = k.es == 8 ? 0 : wg >> bits;
   }
-  return grew;
 }
 
 // ---- whole 16-byte vectors, specialised per element type ------------------------------
 // Candidates that are numerically equivalent but not bit-identical differ almost
 // everywhere, so this path matters as much as the bit-equal one.  A vector is handled in
-// chunks of four elements (two for 8-byte elements).  The common case of a chunk needs no
-// branch and no divide: every element's error is finite and provably cannot raise max_rel;
-// then counting, the first index and max_abs are plain arithmetic.  A chunk in which any
-// lane of the wavefront sees anything else (a possible new maximum, NaN, infinity) is redone
-// element by element with the full rules.
+// chunks of N elements.  The common case of a chunk needs no branch and no divide: every
+// element's error is finite and provably cannot raise max_rel; then the mismatch masks of
+// the lanes are counted on the scalar unit and max_abs is one instruction per element.  Only
+// the elements that may raise max_rel are divided, one per lane and round; a chunk in which
+// any lane sees NaN or infinity is redone element by element under the full rules.
 template <int DT> struct Elem;
 template <> struct Elem<R3_U8>   { static constexpr int size = 1; static constexpr bool is_float = false; };
 template <> struct Elem<R3_F32>  { static constexpr int size = 4; static constexpr bool is_float = true; };
@@ -555,56 +581,7 @@ __device__ __forceinline__ uint64_t elem_bits(const u32x4& v, int e) {
   }
 }
 
-// One element under the full rules, equal or not (the careful path of a chunk).  Returns
-// whether this lane's max_rel grew.
-template <int DT>
-__device__ __forceinline__ bool careful_elem(uint64_t cb, uint64_t gb, uint32_t idx, const ElemKind& k,
-                                             Acc& a) {
-  const bool differ = cb != gb;
-  const double C = to_f64_t<DT>(cb), G = to_f64_t<DT>(gb);
-  const double aG = __builtin_fabs(G);
-  double d = __builtin_fabs(C - G);
-  bool forced = false, rel_done = false, grew = false;
-  if (!(d < kInf)) {  // NaN or +Inf: equal non-finite patterns, a non-finite input, fp64 overflow
-    if (!differ) {
-      d = 0.0;
-    } else if (Elem<DT>::is_float && !(__builtin_fabs(C) < kInf && aG < kInf)) {
-      d = kInf;
-      forced = true;
-      rel_done = true;
-      if (!(a.max_rel == kInf)) {
-        a.max_rel = kInf;
-        a.top = kInf;
-        grew = true;
-      }
-    }
-  }
-  bool mis;
-  if (k.tol) {
-    const double t = k.rtol * aG;
-    const double thr = k.atol + t;
-    mis = forced || d > thr;
-  } else {
-    mis = differ;
-  }
-  if (!rel_done && may_raise_max_rel(d, aG, a.top)) grew |= raise_max_rel(d, aG, a);
-  a.max_abs = d > a.max_abs ? d : a.max_abs;
-  a.count += mis ? 1u : 0u;
-  const uint32_t cand = mis ? idx : 0xFFFFFFFFu;
-  a.first = cand < a.first ? cand : a.first;
-  return grew;
-}
-
-// The wavefront shares its largest max_rel.  Called by all lanes (uniform control flow).
-__device__ __forceinline__ void refresh_top(Acc& a) {
-  const double m = bits_d(dpp_max(dbits(a.max_rel)));
-  if (m > a.top) set_top(a, m);
-}
-__device__ __forceinline__ void refresh_top_if(bool grew, Acc& a) {
-  if (__builtin_amdgcn_ballot_w64(grew) != 0) refresh_top(a);
-}
-
-// A vector is consumed from its low end: drop its first `BYTES` bytes (4, 8 or 16).
+// A vector is consumed from its low end: drop its first BYTES bytes (a multiple of 4).
 template <int BYTES>
 __device__ __forceinline__ void drop_front(u32x4& v) {
   if constexpr (BYTES == 4) {
@@ -627,23 +604,15 @@ __device__ __forceinline__ uint64_t pop_elem(u32x4& v) {
   } else if constexpr (ES == 4) {
     bits = v.x;
     drop_front<4>(v);
-  } else {  // the chunks of 1- and 2-byte elements fit the first two dwords
-    uint64_t w = ((uint64_t)v.y << 32) | v.x;
-    bits = w & ((1ull << (8 * ES)) - 1);
-    w >>= 8 * ES;
-    v.x = (uint32_t)w;
-    v.y = (uint32_t)(w >> 32);
+  } else {
+    constexpr uint32_t S = 8 * ES;
+    bits = v.x & ((1u << S) - 1);
+    v.x = (v.x >> S) | (v.y << (32 - S));
+    v.y = (v.y >> S) | (v.z << (32 - S));
+    v.z = (v.z >> S) | (v.w << (32 - S));
+    v.w >>= S;
   }
   return bits;
-}
-
-// The quick form of may_raise_max_rel for element types of at most 32 significant bits:
-// ph = tq * |G| is exact while it is a normal number or zero, so d <= ph proves
-// d/|G| <= tq <= top (and d == 0 when ph == 0).
-__device__ __forceinline__ bool may_raise_quick(double t, double aG, double tq) {
-  const double ph = tq * aG;
-  const bool exact = __builtin_isnormal(ph) | (ph == 0.0);
-  return !((__builtin_fabs(t) <= ph) & exact);
 }
 
 // max(m, |t|) for a finite t in one instruction (a plain fmax costs a second one that
@@ -662,19 +631,16 @@ __device__ __forceinline__ void compare_chunk(const u32x4& c, const u32x4& g, ui
                                               const ElemKind& k, Acc& a) {
   constexpr bool kQuick = Elem<DT>::size < 8;
   constexpr uint32_t EPV = 16 / Elem<DT>::size;
-  uint64_t cb[N], gb[N];
+  const double top = bits_d(a.top_bits), tq = bits_d(a.tq_bits);
   double aG[N], t[N];  // |G| and the signed difference C - G
   bool any_flag = false;
   bool flag[N];
 #pragma unroll
   for (int e = 0; e < N; ++e) {
-    cb[e] = elem_bits<DT>(c, e);
-    gb[e] = elem_bits<DT>(g, e);
-    const double C = to_f64_t<DT>(cb[e]), G = to_f64_t<DT>(gb[e]);
+    const double C = to_f64_t<DT>(elem_bits<DT>(c, e)), G = to_f64_t<DT>(elem_bits<DT>(g, e));
     aG[e] = __builtin_fabs(G);
     t[e] = C - G;
-    flag[e] = kQuick ? may_raise_quick(t[e], aG[e], a.tq)
-                     : may_raise_max_rel(__builtin_fabs(t[e]), aG[e], a.top);
+    flag[e] = kQuick ? may_raise_quick(t[e], aG[e], tq) : may_raise_max_rel(__builtin_fabs(t[e]), aG[e], top);
     any_flag |= flag[e];
   }
   // Per lane, which of its elements may raise max_rel (or are NaN / infinite).  Usually none.
@@ -684,7 +650,7 @@ __device__ __forceinline__ void compare_chunk(const u32x4& c, const u32x4& g, ui
 #pragma unroll
     for (int e = 0; e < N; ++e) {
       const double d = __builtin_fabs(t[e]);
-      if (kQuick) flag[e] = flag[e] & may_raise_max_rel(d, aG[e], a.top);
+      if (kQuick) flag[e] = flag[e] & may_raise_max_rel(d, aG[e], top);
       odd |= flag[e] & !(d < kInf);
       pend |= flag[e] ? (1u << e) : 0u;
     }
@@ -692,13 +658,13 @@ __device__ __forceinline__ void compare_chunk(const u32x4& c, const u32x4& g, ui
       // The careful path: element by element under the full rules, one copy of the code.
       u32x4 cw = c, gw = g;
       const uint32_t idx = idx0 + lane_id() * EPV;
-      bool grew = false;
+      LaneAcc l{0, 0xFFFFFFFFu, 0.0};
 #pragma unroll 1
       for (uint32_t e = 0; e < (uint32_t)N; ++e) {
         const uint64_t ce = pop_elem<DT>(cw), ge = pop_elem<DT>(gw);
-        grew |= careful_elem<DT>(ce, ge, idx + e, k, a);
+        full_rules(ce != ge, to_f64_t<DT>(ce), to_f64_t<DT>(ge), Elem<DT>::is_float, idx + e, k, a, l);
       }
-      refresh_top_if(grew, a);
+      fold_lanes(a, l);
       return;
     }
   }
@@ -714,7 +680,7 @@ __device__ __forceinline__ void compare_chunk(const u32x4& c, const u32x4& g, ui
     }
   } else {
 #pragma unroll
-    for (int e = 0; e < N; ++e) m[e] = __builtin_amdgcn_ballot_w64(cb[e] != gb[e]);
+    for (int e = 0; e < N; ++e) m[e] = __builtin_amdgcn_ballot_w64(elem_bits<DT>(c, e) != elem_bits<DT>(g, e));
   }
   uint64_t any = 0;
 #pragma unroll
@@ -735,7 +701,7 @@ __device__ __forceinline__ void compare_chunk(const u32x4& c, const u32x4& g, ui
   }
   // The quotients that may raise max_rel, one per lane and round (usually one round).
   if (__builtin_amdgcn_ballot_w64(pend != 0) != 0) {
-    bool grew = false;
+    LaneAcc l{0, 0xFFFFFFFFu, 0.0};
     do {
       if (pend != 0) {
         const uint32_t e = (uint32_t)__builtin_ctz(pend);
@@ -747,10 +713,10 @@ __device__ __forceinline__ void compare_chunk(const u32x4& c, const u32x4& g, ui
           gg = e == (uint32_t)j ? aG[j] : gg;
         }
         const double dd = __builtin_fabs(tt);
-        if (may_raise_max_rel(dd, gg, a.top)) grew |= raise_max_rel(dd, gg, a);
+        if (may_raise_max_rel(dd, gg, lane_top(a, l))) raise_max_rel(dd, gg, l);
       }
     } while (__builtin_amdgcn_ballot_w64(pend != 0) != 0);
-    refresh_top_if(grew, a);
+    fold_lanes(a, l);
   }
 }
 
@@ -759,8 +725,8 @@ __device__ __forceinline__ void compare_chunk(const u32x4& c, const u32x4& g, ui
 template <int DT>
 __device__ __forceinline__ void compare_vector(u32x4 c, u32x4 g, uint32_t idx0, const ElemKind& k, Acc& a) {
   constexpr int ES = Elem<DT>::size;
-  constexpr int N = ES == 8 ? 2 : 4;         // elements per chunk
-  constexpr int CHUNKS = 16 / (ES * N);      // 1, 1, 2, 4 for 8-, 4-, 2-, 1-byte elements
+  constexpr int N = ES == 8 ? 2 : ES == 4 ? 4 : 8;  // elements per chunk
+  constexpr int CHUNKS = 16 / (ES * N);             // 2 for 1-byte elements, else 1
   if constexpr (CHUNKS == 1) {
     compare_chunk<DT, N>(c, g, idx0, k, a);
   } else {
@@ -869,18 +835,21 @@ __device__ __forceinline__ void compare_tile(const uint8_t* cbase, const uint8_t
   const uint32_t nwords = (len + 7) >> 3;
   const uint32_t trips = (nwords - first_word + 63) >> 6;
   uint32_t j = first_word + lane;
+  LaneAcc l{0, 0xFFFFFFFFu, 0.0};
   for (uint32_t it = 0; it < trips; ++it, j += 64) {
-    bool grew = false;
     if (j < nwords) {
       const uint32_t at = 8 * j;
       const uint32_t valid = (len - at) < 8 ? (len - at) : 8;
       const uint64_t wc = load_word_any(cbase + at, valid, k.es);
       const uint64_t wg = load_word_any(gbase + at, valid, k.es);
       a.cks += cks_term((uint32_t)wc, (uint32_t)(wc >> 32), (word0 + j + 1) * kPhi);
-      grew = differing_word(wc, wg, valid / k.es, j * epw, k, a);
+      differing_word(wc, wg, valid / k.es, j * epw, k, a, l);
     }
-    refresh_top_if(grew, a);
+    // share the relative error found so far: it spares the later words their divides
+    if (__builtin_amdgcn_ballot_w64(l.max_rel > bits_d(a.top_bits)) != 0)
+      raise_top(a, bits_d(dpp_max(dbits(l.max_rel))));
   }
+  if (trips) fold_lanes(a, l);
 }
 
 // Validate one tile and leave its partial at *dst (all 64 lanes of the wavefront take part).
@@ -897,31 +866,21 @@ __device__ __forceinline__ void compare_tile_to_partial(const TileView& tv, cons
   k.rtol = tv.rtol;
   k.atol = tv.atol;
   Acc a;
-  a.count = 0;
-  a.first = 0xFFFFFFFFu;
   a.wcount = 0;
   a.wfirst = 0xFFFFFFFFu;
+  a.top_bits = 0;
+  a.tq_bits = 0;
   a.max_abs = 0.0;
-  a.max_rel = 0.0;
-  a.top = 0.0;
-  a.tq = 0.0;
   a.cks = 0;
   compare_tile(live + at, golden + at, tv.len, word0, k, lane, a);
-  // Fold the wavefront.  A tile in which no lane saw a differing element (the usual case)
-  // only has a checksum to add up.
+  // Fold the two per-lane values.  A tile in which nothing differed (the usual case) only
+  // has a checksum to add up.
   const uint64_t cks = dpp_sum(a.cks);
-  const bool touched = a.count != 0 || a.first != 0xFFFFFFFFu || dbits(a.max_abs) != 0 ||
-                       dbits(a.max_rel) != 0;
-  uint64_t count = a.wcount, first_elem = R3_NO_INDEX, max_abs = 0, max_rel = 0;
-  uint32_t first = a.wfirst;
-  if (__builtin_amdgcn_ballot_w64(touched) != 0) {
-    count += dpp_sum(a.count);
-    const uint32_t lane_first = dpp_min(a.first);
-    first = lane_first < first ? lane_first : first;
-    max_abs = dpp_max(dbits(a.max_abs));
-    max_rel = dpp_max(dbits(a.max_rel));
-  }
-  if (first != 0xFFFFFFFFu) first_elem = tv.rel_start / k.es + first;
+  uint64_t max_abs = 0;
+  if (__builtin_amdgcn_ballot_w64(dbits(a.max_abs) != 0) != 0) max_abs = dpp_max(dbits(a.max_abs));
+  const uint64_t count = a.wcount;
+  const uint64_t first_elem = a.wfirst != 0xFFFFFFFFu ? tv.rel_start / k.es + a.wfirst : R3_NO_INDEX;
+  const uint64_t max_rel = a.top_bits;
   uint64_t* out = (uint64_t*)dst;
   if (lane < 5) {
     const uint64_t val = lane == 0 ? count : lane == 1 ? first_elem : lane == 2 ? max_abs
