@@ -239,6 +239,18 @@ class Replay:
                                    self.d_regions_ring[slot])
         return t, i, k
 
+    def submit_overlapped(self, i, slot):
+        """The same evaluation through the double-buffered pipeline: live arenas alternate."""
+        k = i % len(self.candidates)
+        while len(self.d_regions_ring) <= slot:
+            self.d_regions_ring.append(self.torch.zeros_like(self.d_regions))
+        if getattr(self, "d_live_pair", None) is None:
+            self.d_live_pair = [self.d_live, self.d_live.clone()]
+        t = self.r3.r3_eval_submit_overlapped(self.ctx, self.restore_tbl, self.d_pro, self.check_tbl, self.d_epi,
+                                              self.d_live_pair[i % 2], self.launch, self.candidates[k], 0, 1,
+                                              self.r3.EVERY, self.d_regions_ring[slot])
+        return t, i, k
+
     def finish(self, t, i, k):
         rc, out = self.r3.r3_eval_wait(self.ctx, t)
         want = self.expect_pass[k]
@@ -262,6 +274,29 @@ def run_steps(rp, n, inflight):
             rp.finish(*q.popleft())
     while q:
         rp.finish(*q.popleft())
+
+
+def overlapped_leg(rp, steps, warmup, inflight=2):
+    """Evaluations/s with two live arenas on the context's two streams (restore of one evaluation
+    beside the validation of the one before; candidates still alone on the GPU)."""
+    torch = rp.torch
+
+    def run(n):
+        q = collections.deque()
+        for i in range(n):
+            q.append(rp.submit_overlapped(i, i % inflight))
+            if len(q) == inflight:
+                rp.finish(*q.popleft())
+        while q:
+            rp.finish(*q.popleft())
+    run(warmup + (warmup & 1))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(steps)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    return {"value": steps / dt, "unit": "evals/s", "ms_per_step": dt / steps * 1e3, "steps": steps,
+            "evaluations_in_flight": inflight}
 
 
 def timed_run(rp, steps, warmup, inflight=1):
@@ -664,6 +699,8 @@ def other_legs(r3, wl, ctx, torch, skip, inflight, defaults, ceil, with_cpu):
         if inflight > 1:
             dt1, _ = timed_run(rp, steps, warmup, 1)
             leg["synchronous"] = {"value": steps / dt1, "unit": "evals/s", "ms_per_step": dt1 / steps * 1e3}
+        if name != "large_snapshot":
+            leg["overlapped"] = overlapped_leg(rp, steps, warmup, max(2, inflight))
         if with_cpu:
             leg["cpu_baseline"] = cpu_baseline(rp, budget_s=3.0)
         if name in ("jacobi", "spmv"):
@@ -732,6 +769,8 @@ def main():
         dt1, _ = timed_run(rp, steps, warmup, 1)
         line["synchronous"] = {"value": steps / dt1, "unit": "evals/s", "ms_per_step": dt1 / steps * 1e3,
                                "note": "the same evaluations through r3_eval_candidate, one at a time"}
+    if a.workload != "large_snapshot":
+        line["overlapped"] = overlapped_leg(rp, steps, warmup, max(2, a.inflight))
     line["cpu_baseline"] = None if a.no_cpu else cpu_baseline(rp)
     line["record_path"] = record_path_leg(rp, reps=3 if a.workload == "large_snapshot" else 10)
     if a.workload in ("jacobi", "spmv"):

@@ -326,6 +326,29 @@ int r3_eval_submit(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prolo
 int r3_eval_wait(r3_ctx* ctx, uint32_t ticket, r3_eval_result* host_out,
                  r3_guard_result* host_guard_out);
 
+/* r3_eval_submit with double-buffered live memory (Section V-D: the replay server keeps state
+ * resident and pre-allocated so that nothing of one evaluation's set-up and tear-down has to
+ * wait for another's).  The caller keeps TWO live arenas and passes them alternately; the
+ * context owns two streams (default priority) and runs consecutive overlapped evaluations on
+ * them alternately, after the work that `stream` holds at submission.  Ordering between
+ * evaluation k and k+1:
+ *   - the first restore of k+1 starts when the last candidate launch of k has finished, so it
+ *     overlaps the last validation of k;
+ *   - the first candidate launch of k+1 starts when that validation has finished: a timed
+ *     candidate never shares the GPU with restore or validation work of this library.
+ * Two consecutive submissions must therefore name different d_live (the same one is legal but
+ * serialises nothing less: it races), and different d_regions if both results are wanted;
+ * tables and snapshots may be shared.  This pays when restore and validation are bound by
+ * latency (small states); for large states both are bound by HBM bandwidth and the overlap
+ * gains nothing.  Tickets, r3_eval_wait and the error rules are those of r3_eval_submit; the
+ * results are complete when r3_eval_wait returns (later work on `stream` is not ordered after
+ * them). */
+int r3_eval_submit_overlapped(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
+                              const r3_table* check_tbl, const void* d_epilogue, void* d_live,
+                              r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
+                              uint32_t compare_policy, r3_region_result* d_regions,
+                              uint32_t* ticket_out, void* stream);
+
 /* r3_eval_wait that gives up: looks for the evaluation's end for at most timeout_us
  * microseconds (0 = look once).  Finished: behaves exactly like r3_eval_wait.  Not finished:
  * R3_EBUSY, nothing is written, the ticket stays outstanding and can be waited for again.

@@ -76,7 +76,7 @@ DECLARED = [
     "r3_writeset_regions", "r3_eval_candidate_guarded", "r3_table_replicate",
     "r3_eval_candidate_instances", "r3_ctx_last_times", "r3_timing_stats",
     "r3_replay_workspace_bytes", "r3_replay_create", "r3_replay_run", "r3_replay_destroy",
-    "r3_compare_static",
+    "r3_compare_static", "r3_eval_submit_overlapped",
 ]
 
 _lib = None
@@ -128,6 +128,8 @@ def lib():
                                         ctypes.POINTER(EvalResult), vp]
         L.r3_eval_submit.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, u32, vp,
                                      ctypes.POINTER(u32), vp]
+        L.r3_eval_submit_overlapped.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, u32, vp,
+                                                ctypes.POINTER(u32), vp]
         L.r3_eval_wait.argtypes = [vp, u32, ctypes.POINTER(EvalResult), ctypes.POINTER(GuardResult)]
         L.r3_eval_try_wait.argtypes = [vp, u32, u32, ctypes.POINTER(EvalResult), ctypes.POINTER(GuardResult)]
         L.r3_eval_submit_guarded.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, u32, vp,
@@ -432,6 +434,23 @@ def r3_eval_submit(ctx, restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, 
                               _ptr(d_regions), ctypes.byref(ticket), _stream(stream))
     del keep
     ctx.check(rc, "r3_eval_submit")
+    return ticket.value
+
+
+def r3_eval_submit_overlapped(ctx, restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, launch, user,
+                              warmup, reps, policy, d_regions, stream=None):
+    """r3_eval_submit on the context's two streams (pass two live arenas alternately)."""
+    _need(d_prologue, restore_tbl.arena_bytes, "prologue")
+    _need(d_epilogue, check_tbl.arena_bytes, "epilogue")
+    _need(d_live, max(restore_tbl.arena_bytes, check_tbl.arena_bytes), "live arena")
+    _need(d_regions, 40 * check_tbl.n, "region results")
+    fn, usr, keep = _launch_args(launch, user)
+    ticket = ctypes.c_uint32(0)
+    rc = lib().r3_eval_submit_overlapped(ctx.handle, restore_tbl.handle, _ptr(d_prologue), check_tbl.handle,
+                                         _ptr(d_epilogue), _ptr(d_live), fn, _ptr(usr), warmup, reps, policy,
+                                         _ptr(d_regions), ctypes.byref(ticket), _stream(stream))
+    del keep
+    ctx.check(rc, "r3_eval_submit_overlapped")
     return ticket.value
 
 

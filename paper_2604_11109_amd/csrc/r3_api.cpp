@@ -69,6 +69,34 @@ int lane_init(r3_ctx* ctx, r3::EvalLane& lane) {
   return R3_OK;
 }
 
+// The context's own pair of streams and ordering events, created at the first overlapped
+// submission.  Default priority, like every stream this library touches.
+int pipe_init(r3_ctx* ctx) {
+  r3::Pipe& p = ctx->pipe;
+  if (p.ready) return R3_OK;
+  hipError_t e = hipSuccess;
+  for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+    e = hipStreamCreateWithFlags(&p.s[i], hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&p.cand_end[i], hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&p.val_end[i], hipEventDisableTiming);
+  }
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&p.join, hipEventDisableTiming);
+  if (e != hipSuccess) return fail_hip(ctx, e, "streams of the overlapped pipeline");
+  p.ready = true;
+  return R3_OK;
+}
+
+void pipe_release(r3::Pipe& p) {
+  for (int i = 0; i < 2; ++i) {
+    if (p.s[i]) (void)hipStreamSynchronize(p.s[i]);
+    if (p.cand_end[i]) (void)hipEventDestroy(p.cand_end[i]);
+    if (p.val_end[i]) (void)hipEventDestroy(p.val_end[i]);
+    if (p.s[i]) (void)hipStreamDestroy(p.s[i]);
+  }
+  if (p.join) (void)hipEventDestroy(p.join);
+  p = r3::Pipe{};
+}
+
 void lane_release(r3::EvalLane& lane) {
   for (hipEvent_t e : lane.events) (void)hipEventDestroy(e);
   lane.events.clear();
@@ -128,6 +156,7 @@ int r3_ctx_destroy(r3_ctx* ctx) {
   for (r3::EvalLane& lane : ctx->lanes)
     if (lane.busy) (void)hipStreamSynchronize(lane.stream);
   for (r3::EvalLane& lane : ctx->lanes) lane_release(lane);
+  pipe_release(ctx->pipe);
   delete ctx;
   return R3_OK;
 }
@@ -381,7 +410,8 @@ static int eval_enqueue(r3_ctx* ctx, r3::EvalLane& lane, const r3_table* restore
                         const r3_table* check_tbl, const void* d_epilogue, void* d_live,
                         r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
                         uint32_t compare_policy, r3_region_result* d_regions, const r3_guard* guard,
-                        uint32_t instances, uint64_t instance_stride, bool mark_end, void* stream) {
+                        uint32_t instances, uint64_t instance_stride, bool mark_end, void* stream,
+                        bool overlapped = false) {
   int rc = check_common(ctx, restore_tbl);
   if (rc == R3_OK) rc = check_common(ctx, check_tbl);
   if (rc != R3_OK) return rc;
@@ -406,6 +436,27 @@ static int eval_enqueue(r3_ctx* ctx, r3::EvalLane& lane, const r3_table* restore
   rc = lane_init(ctx, lane);
   if (rc != R3_OK) return rc;
   hipStream_t s = as_stream(stream);
+  // Overlapped: the evaluation runs on one of the context's two streams, after what the
+  // caller's stream holds now.  Its first restore waits for the previous evaluation's last
+  // candidate (a restore never runs beside a timed candidate) and may overlap that
+  // evaluation's last validation; its first candidate waits for that validation.
+  r3::Pipe& pipe = ctx->pipe;
+  const uint32_t side = overlapped ? (uint32_t)(pipe.n & 1) : 0, other = side ^ 1;
+  if (overlapped) {
+    rc = pipe_init(ctx);
+    if (rc != R3_OK) return rc;
+    // nothing to wait for when the caller's stream is idle (the usual state inside a search loop)
+    hipError_t je = hipStreamQuery(s);
+    if (je == hipErrorNotReady) {
+      je = hipEventRecord(pipe.join, s);
+      if (je == hipSuccess) je = hipStreamWaitEvent(pipe.s[side], pipe.join, 0);
+    }
+    s = pipe.s[side];
+    if (je == hipSuccess && pipe.cand_valid[other]) je = hipStreamWaitEvent(s, pipe.cand_end[other], 0);
+    if (je != hipSuccess) return fail_hip(ctx, je, "overlapped pipeline ordering");
+    stream = reinterpret_cast<void*>(s);
+    pipe.cand_valid[side] = false;
+  }
   // Events of replay r: [4r] before the restore and [4r+3] after the validation (only when
   // profiling), [4r+1] / [4r+2] around the candidate.
   const bool prof = ctx->profile_period != 0 && (ctx->evals++ % ctx->profile_period) == 0;
@@ -444,6 +495,13 @@ static int eval_enqueue(r3_ctx* ctx, r3::EvalLane& lane, const r3_table* restore
     }
     e = r3::launch_restore(restore_tbl->dev, restore_tbl->class_count, d_prologue, d_live, s);
     if (e != hipSuccess) break;
+    if (overlapped && rep == 0 && launch && pipe.val_valid[other]) {
+      // The candidate runs alone: it waits for what the other stream holds now, which ends with the
+      // previous evaluation's last validation (recorded only here, where it is needed).
+      e = hipEventRecord(pipe.val_end[other], pipe.s[other]);
+      if (e == hipSuccess) e = hipStreamWaitEvent(s, pipe.val_end[other], 0);
+      if (e != hipSuccess) break;
+    }
     if (launch || prof) {
       e = hipEventRecord(lane.events[4 * rep + 1], s);
       if (e != hipSuccess) break;
@@ -459,6 +517,11 @@ static int eval_enqueue(r3_ctx* ctx, r3::EvalLane& lane, const r3_table* restore
     if (launch || prof) {
       e = hipEventRecord(lane.events[4 * rep + 2], s);
       if (e != hipSuccess) break;
+    }
+    if (overlapped && launch && rep == total - 1) {  // the next evaluation's restore may start here
+      e = hipEventRecord(pipe.cand_end[side], s);
+      if (e != hipSuccess) break;
+      pipe.cand_valid[side] = true;
     }
     const bool validate = compare_policy == R3_POLICY_EVERY ||
                           (compare_policy == R3_POLICY_FIRST && rep == 0) ||
@@ -487,6 +550,12 @@ static int eval_enqueue(r3_ctx* ctx, r3::EvalLane& lane, const r3_table* restore
       lane.last_want = ctx->seq;
     }
     ++lane.done;
+  }
+  if (overlapped) {
+    // what the next overlapped evaluation has to wait for
+    pipe.val_valid[side] = true;  // this stream now holds work a later candidate must wait for
+    if (e != hipSuccess || cand != 0 || !launch) pipe.cand_valid[side] = false;
+    ++pipe.n;
   }
   lane.cand = cand;
   lane.status = e;
@@ -632,7 +701,8 @@ static int eval_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_pro
 static int submit_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
                        const r3_table* check_tbl, const void* d_epilogue, void* d_live, r3_launch_fn launch,
                        void* user, uint32_t warmup, uint32_t reps, uint32_t compare_policy,
-                       r3_region_result* d_regions, const r3_guard* guard, uint32_t* ticket_out, void* stream) {
+                       r3_region_result* d_regions, const r3_guard* guard, uint32_t* ticket_out, void* stream,
+                       bool overlapped = false) {
   if (ctx == nullptr) return R3_EINVAL;
   if (ticket_out == nullptr) return fail(ctx, R3_EINVAL, "pointer is NULL");
   *ticket_out = 0;
@@ -641,7 +711,7 @@ static int submit_impl(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_p
     if (!ctx->lanes[i].busy) lane = i;
   if (lane == 0) return fail(ctx, R3_ENOSPC, "R3_MAX_INFLIGHT evaluations are in flight already");
   int rc = eval_enqueue(ctx, ctx->lanes[lane], restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, launch,
-                        user, warmup, reps, compare_policy, d_regions, guard, 1, 0, true, stream);
+                        user, warmup, reps, compare_policy, d_regions, guard, 1, 0, true, stream, overlapped);
   if (rc == R3_OK) *ticket_out = lane;
   return rc;
 }
@@ -652,6 +722,15 @@ int r3_eval_submit(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prolo
                    r3_region_result* d_regions, uint32_t* ticket_out, void* stream) {
   return submit_impl(ctx, restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, launch, user, warmup, reps,
                      compare_policy, d_regions, nullptr, ticket_out, stream);
+}
+
+int r3_eval_submit_overlapped(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,
+                              const r3_table* check_tbl, const void* d_epilogue, void* d_live,
+                              r3_launch_fn launch, void* user, uint32_t warmup, uint32_t reps,
+                              uint32_t compare_policy, r3_region_result* d_regions, uint32_t* ticket_out,
+                              void* stream) {
+  return submit_impl(ctx, restore_tbl, d_prologue, check_tbl, d_epilogue, d_live, launch, user, warmup, reps,
+                     compare_policy, d_regions, nullptr, ticket_out, stream, true);
 }
 
 int r3_eval_submit_guarded(r3_ctx* ctx, const r3_table* restore_tbl, const void* d_prologue,

@@ -191,6 +191,23 @@ struct EvalLane {
 
 }  // namespace r3
 
+namespace r3 {
+
+// Two streams of the context's own on which consecutive overlapped evaluations alternate, and
+// the events that keep the timed candidate alone on the GPU (r3_eval_submit_overlapped).
+struct Pipe {
+  hipStream_t s[2] = {nullptr, nullptr};
+  hipEvent_t cand_end[2] = {nullptr, nullptr};  // after the last candidate launch of an evaluation
+  hipEvent_t val_end[2] = {nullptr, nullptr};   // after its last validation
+  hipEvent_t join = nullptr;                    // the caller's stream at submission
+  bool cand_valid[2] = {false, false};
+  bool val_valid[2] = {false, false};
+  uint64_t n = 0;                               // evaluations submitted this way
+  bool ready = false;
+};
+
+}  // namespace r3
+
 struct r3_ctx {
   int device = 0;
   std::string err;
@@ -200,6 +217,7 @@ struct r3_ctx {
   uint32_t profile_period = 0;         // 0 = off, n = stage events on every n-th evaluation
   uint64_t evals = 0;
   r3_profile profile{};
+  r3::Pipe pipe;
   r3::Partial* static_scratch = nullptr;  // this device's copy of the library's partials buffer
   hipError_t static_scratch_status = hipSuccess;
 };

@@ -361,3 +361,105 @@ def test_try_wait_gives_up_and_can_be_repeated(env, oracle):
     assert r3.r3_eval_try_wait(ctx, t, 0) is None
     rc, out = r3.r3_eval_wait(ctx, t)
     assert rc == r3.OK and out.total_mismatch == ref.total_mismatch
+
+
+@pytest.mark.parametrize("n", [40, 128])
+def test_overlapped_evaluations_on_two_live_arenas(env, oracle, n):
+    """r3_eval_submit_overlapped: consecutive evaluations alternate between two live arenas and the
+    context's two streams; every ticket's verdict, region results and final live state must be what the
+    oracle's evaluation loop gives for that candidate, whatever the order the tickets are waited for in."""
+    r3, wl, ctx, torch = env
+    c = ri.jacobi(n)
+    A = c["arena_bytes"]
+    rt = r3.Table(ctx, c["restore_rows"], A)
+    ct = r3.Table(ctx, c["check_rows"], A)
+    d_live = [torch.full((A,), 0x11 * (i + 1), dtype=torch.uint8, device="cuda:0") for i in range(2)]
+    d_live[0].copy_(dev(torch, c["prologue"]))
+    d_pro = torch.empty(A, dtype=torch.uint8, device="cuda:0")
+    d_epi = torch.empty(A, dtype=torch.uint8, device="cuda:0")
+    r3.r3_record(ctx, rt, d_live[0], wl.jacobi_launch(), wl.jacobi_args(c, 64, 1, 0), d_pro, d_epi)
+    pro, epi = host(d_pro), host(d_epi)
+    variants = list(ri.JACOBI_VARIANTS)                     # the last one carries the planted bug
+    plans = [(0, 1, r3.EVERY), (1, 2, r3.EVERY), (0, 3, r3.LAST), (2, 1, r3.FIRST)]
+    args = [wl.jacobi_args(c, b, u, g) for b, u, g in variants]
+    d_regions = [torch.zeros(40 * ct.n, dtype=torch.uint8, device="cuda:0") for _ in variants]
+
+    def cpu_candidate(bug):
+        def run(live):
+            g = live[c["in_off"]:c["in_off"] + c["grid_bytes"]].view("<f8").reshape(n, n, n)
+            out = live[c["out_off"]:c["out_off"] + c["grid_bytes"]].view("<f8").reshape(n, n, n)
+            ref = ri.jacobi_reference(g)
+            if bug:
+                ref[:, :, n - 2] = out[:, :, n - 2]      # the x loop stops one short: old values stay
+            out[...] = ref
+            return 0
+        return run
+
+    for order in ([0, 1, 2, 3, 4, 5, 6, 7], [7, 6, 5, 4, 3, 2, 1, 0], [1, 0, 3, 2, 5, 4, 7, 6]):
+        print("case overlapped", n, order, flush=True)
+        tickets = []
+        for k, a in enumerate(args):
+            warmup, reps, policy = plans[k % len(plans)]
+            tickets.append(r3.r3_eval_submit_overlapped(ctx, rt, d_pro, ct, d_epi, d_live[k % 2], wl.jacobi_launch(), a,
+                                                        warmup, reps, policy, d_regions[k]))
+        outs = {}
+        for k in order:
+            outs[k] = r3.r3_eval_wait(ctx, tickets[k])
+        torch.cuda.synchronize()
+        lives = [None, None]
+        for k, (b, u, bug) in enumerate(variants):
+            warmup, reps, policy = plans[k % len(plans)]
+            live = np.full(A, 0xEE, np.uint8)
+            exp = oracle.eval_candidate(oracle.make_table(c["restore_rows"]), pro, oracle.make_table(c["check_rows"]),
+                                        epi, live, cpu_candidate(bug), warmup, reps, policy)
+            lives[k % 2] = live
+            rc, out = outs[k]
+            what = "evaluation %d (block %d unroll %d bug %d)" % (k, b, u, bug)
+            assert rc == r3.OK, what
+            assert out.total_mismatch == exp["total_mismatch"], what
+            assert out.passed == exp["pass"] == int(not bug), what
+            assert (out.first_region, out.first_index) == (exp["first_region"], exp["first_index"]), what
+            assert_results_equal(r3.results_to_numpy(d_regions[k], ct.n), exp["regions"], what)
+            assert out.ms_min > 0 and out.ms_min <= out.ms_median <= out.ms_max, what
+        for i in range(2):
+            assert (host(d_live[i]) == lives[i]).all(), "live arena %d" % i
+    # the plain calls still work beside it, on the caller's stream
+    rc, out = r3.r3_eval_candidate(ctx, rt, d_pro, ct, d_epi, d_live[0], wl.jacobi_launch(), args[0], 0, 1, r3.EVERY,
+                                   d_regions[0])
+    assert rc == r3.OK and out.passed == 1
+
+
+def test_overlapped_pure_replays_and_failing_candidate(env, oracle):
+    """Overlapped submissions without a candidate (restore -> validate only), and one whose launch fails:
+    the failure is reported by its wait and the evaluations around it are not disturbed."""
+    r3, wl, ctx, torch = env
+    c = ri.replay_small(n=1 << 15)
+    A = c["arena_bytes"]
+    rt, ct = r3.Table(ctx, c["restore_rows"], A), r3.Table(ctx, c["check_rows"], A)
+    d_pro, d_epi = dev(torch, c["prologue"]), dev(torch, c["epilogue"])
+    d_live = [dev(torch, c["live"]), dev(torch, c["live"])]
+    d_regions = [torch.zeros(40 * ct.n, dtype=torch.uint8, device="cuda:0") for _ in range(6)]
+    live = c["live"].copy()
+    exp = oracle.eval_candidate(oracle.make_table(c["restore_rows"]), c["prologue"], oracle.make_table(c["check_rows"]),
+                                c["epilogue"], live, None, 0, 2)
+    code = ctypes.c_int(9)
+    tickets = []
+    for k in range(6):
+        if k == 3:
+            tickets.append(r3.r3_eval_submit_overlapped(ctx, rt, d_pro, ct, d_epi, d_live[k % 2], wl.failing_launch(),
+                                                        ctypes.addressof(code), 0, 2, r3.EVERY, d_regions[k]))
+        else:
+            tickets.append(r3.r3_eval_submit_overlapped(ctx, rt, d_pro, ct, d_epi, d_live[k % 2], None, None, 0, 2,
+                                                        r3.EVERY, d_regions[k]))
+    for k in (5, 0, 3, 1, 4, 2):
+        rc, out = r3.r3_eval_wait(ctx, tickets[k])
+        if k == 3:
+            assert rc == r3.ECANDIDATE and out.passed == 0 and out.candidate_status == 9
+            continue
+        assert rc == r3.OK
+        assert out.total_mismatch == exp["total_mismatch"] == c["n_planted"] and out.passed == 0
+        assert out.first_index == exp["first_index"]
+        assert_results_equal(r3.results_to_numpy(d_regions[k], ct.n), exp["regions"], "pure replay %d" % k)
+    torch.cuda.synchronize()
+    for i in range(2):
+        assert (host(d_live[i]) == live).all()
