@@ -645,11 +645,17 @@ static int eval_collect(r3_ctx* ctx, r3::EvalLane& lane, r3_eval_result* host_ou
   // Candidate times of the replays after the warm-up that ran to the end.
   ctx->last_times.clear();
   if (lane.has_launch) {
+    // The verdict may have arrived by polling pinned memory, which says nothing about event
+    // state: wait for the last candidate's end event (it has passed; this is cheap) before
+    // reading times, and refuse to report a runtime that is not there (a search that keeps the
+    // fastest correct candidate must never see a zero).
+    if (done > 0) (void)hipEventSynchronize(lane.events[4 * (done - 1) + 2]);
     std::vector<float> ms;
     for (uint32_t rep = lane.warmup; rep < done; ++rep) {
       float t = 0.f;
-      if (hipEventElapsedTime(&t, lane.events[4 * rep + 1], lane.events[4 * rep + 2]) == hipSuccess)
-        ms.push_back(t);
+      const hipError_t te = hipEventElapsedTime(&t, lane.events[4 * rep + 1], lane.events[4 * rep + 2]);
+      if (te != hipSuccess) return fail_hip(ctx, te, "candidate time of a finished replay");
+      ms.push_back(t);
     }
     ctx->last_times = ms;
     if (!ms.empty()) {

@@ -387,7 +387,11 @@ struct Acc {
   uint32_t wcount;    // mismatches so far
   uint32_t wfirst;    // smallest mismatching element index inside the tile, ~0u if none
   uint64_t top_bits;  // bit pattern of top = the largest relative error so far (the tile's max_rel)
-  uint64_t tq_bits;   // bit pattern of tq = top cut down so that tq * |G| is exact (set_top)
+  uint64_t tq_bits;   // bit pattern of tq = top cut down so that tq * |G| is exact (raise_top)
+  uint32_t tq_fix;    // floor(top * 2^16), saturated: the same bound in fixed point, for 1-byte elements
+  uint32_t lut_ready; // 1 once this wavefront has built its table of the 1-byte path
+  uint32_t lut_fix;   // the tq_fix that table was built for
+  uint32_t imax;      // per lane: largest integer error seen by the 1-byte path
   double max_abs;     // per lane
   uint64_t cks;       // per lane
 };
@@ -406,6 +410,7 @@ struct ElemKind {
   bool is_float;
   bool tol;
   double rtol, atol;
+  uint32_t* lut;      // this wavefront's 512 bytes of LDS (table of the 1-byte path)
 };
 
 // binary16 -> binary64 (exact): through the hardware conversion to binary32.
@@ -463,6 +468,8 @@ __device__ __forceinline__ void raise_top(Acc& a, double m) {
     a.top_bits = sgpr(mb);
     const uint64_t cut = m < kInf ? (mb & ~0xFFFFFFFFull) : dbits(0x1p500);
     a.tq_bits = sgpr(cut);
+    const uint32_t fix = m < 0x1p15 ? (uint32_t)(m * 0x1p16) : 0x7FFFFFFFu;  // the scaling is exact
+    a.tq_fix = sgpr(fix);
   }
 }
 
@@ -549,7 +556,7 @@ __device__ __forceinline__ void differing_word(uint64_t wc, uint64_t wg, uint32_
 // the elements that may raise max_rel are divided, one per lane and round; a chunk in which
 // any lane sees NaN or infinity is redone element by element under the full rules.
 template <int DT> struct Elem;
-template <> struct Elem<R3_U8>   { static constexpr int size = 1; static constexpr bool is_float = false; };
+template <> struct Elem<R3_U8>   { static constexpr int size = 1; [[maybe_unused]] static constexpr bool is_float = false; };
 template <> struct Elem<R3_F32>  { static constexpr int size = 4; static constexpr bool is_float = true; };
 template <> struct Elem<R3_F64>  { static constexpr int size = 8; static constexpr bool is_float = true; };
 template <> struct Elem<R3_I32>  { static constexpr int size = 4; static constexpr bool is_float = false; };
@@ -720,6 +727,100 @@ __device__ __forceinline__ void compare_chunk(const u32x4& c, const u32x4& g, ui
   }
 }
 
+// ---- 1-byte elements: the same chunk in integer arithmetic -----------------------------
+// With C, G in 0..255 everything is exact in small integers: d = |C - G|, and both tests of
+// an element are comparisons of d with a function of G alone, read from a 256-entry table
+// that the wavefront keeps in LDS (two bytes per entry):
+//   T[G] = min(255, floor(atol + fl(rtol*G)))      mismatch under tolerance  <=>  d > T[G]
+//          (binary64, the two roundings of the rule; d is an integer, so d > thr <=> d > floor(thr);
+//          T[G] = 0 in bitwise mode, where any difference is a mismatch)
+//   Q[G] = min(255, floor(F * max(G, 1) / 2^16)),  F = floor(top * 2^16)
+//          d <= Q[G]  =>  d * 2^16 <= F * G  =>  d/G <= top: the quotient cannot raise max_rel.
+//          G == 0 (no relative error by rule) is entered as G = 1, which flags it only when d
+//          itself exceeds top.
+// Elements with d > Q[G] take the exact test and the divide like those of every other type.
+// The table is rebuilt when top has changed (a few times per tile).
+__device__ __forceinline__ void build_byte_table(const ElemKind& k, Acc& a) {
+  if (a.lut_ready && a.lut_fix == a.tq_fix) return;
+  const uint32_t lane = lane_id();
+  uint32_t entry[4];
+#pragma unroll
+  for (uint32_t j = 0; j < 4; ++j) {
+    const uint32_t gi = 4 * lane + j;
+    const double G = (double)gi;
+    const double rt = k.rtol * G;
+    const double thr = k.atol + rt;
+    // thr >= 0: truncation is floor.  Bitwise mode: T = 0, any difference is a mismatch.
+    const uint32_t T = !k.tol ? 0u : thr >= 255.0 ? 255u : (uint32_t)thr;
+    const uint64_t q = ((uint64_t)a.tq_fix * (gi > 1u ? gi : 1u)) >> 16;
+    const uint32_t Q = q > 255u ? 255u : (uint32_t)q;
+    entry[j] = T | (Q << 8);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // earlier reads of the table are done
+  k.lut[2 * lane] = entry[0] | (entry[1] << 16);
+  k.lut[2 * lane + 1] = entry[2] | (entry[3] << 16);
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  a.lut_ready = 1;
+  a.lut_fix = a.tq_fix;
+}
+
+template <int N>  // the first N (<= 8) bytes of c and g
+__device__ __forceinline__ void compare_chunk_u8(const u32x4& c, const u32x4& g, uint32_t idx0,
+                                                 const ElemKind& k, Acc& a) {
+  constexpr uint32_t EPV = 16;
+  uint32_t ge[N], d[N], tv[N];
+  uint64_t m[N];
+  const uint16_t* lut = (const uint16_t*)k.lut;
+  build_byte_table(k, a);
+#pragma unroll
+  for (int e = 0; e < N; ++e) {
+    const uint32_t ce = (c[e >> 2] >> (8 * (e & 3))) & 0xFFu;
+    ge[e] = (g[e >> 2] >> (8 * (e & 3))) & 0xFFu;
+    d[e] = ce > ge[e] ? ce - ge[e] : ge[e] - ce;
+    a.imax = d[e] > a.imax ? d[e] : a.imax;
+  }
+#pragma unroll
+  for (int e = 0; e < N; ++e) tv[e] = lut[ge[e]];  // all table reads first: one wait for the N of them
+  uint64_t any = 0, any_rel = 0;
+#pragma unroll
+  for (int e = 0; e < N; ++e) {
+    m[e] = __builtin_amdgcn_ballot_w64(d[e] > (tv[e] & 0xFFu));
+    any_rel |= __builtin_amdgcn_ballot_w64(d[e] > (tv[e] >> 8));
+    any |= m[e];
+    a.wcount += (uint32_t)__builtin_popcountll(m[e]);
+  }
+  if (any != 0 && idx0 < a.wfirst) {
+    const uint32_t lane = (uint32_t)__builtin_ctzll(any);
+    uint32_t e0 = N - 1;
+#pragma unroll
+    for (int e = N - 2; e >= 0; --e) e0 = ((m[e] >> lane) & 1) ? (uint32_t)e : e0;
+    const uint32_t cand = idx0 + lane * EPV + e0;
+    a.wfirst = cand < a.wfirst ? cand : a.wfirst;
+  }
+  if (any_rel != 0) {
+    uint32_t pend = 0;
+#pragma unroll
+    for (int e = 0; e < N; ++e) pend |= d[e] > (tv[e] >> 8) ? (1u << e) : 0u;
+    LaneAcc l{0, 0xFFFFFFFFu, 0.0};
+    do {
+      if (pend != 0) {
+        const uint32_t e = (uint32_t)__builtin_ctz(pend);
+        pend &= pend - 1;
+        uint32_t di = d[0], gi = ge[0];
+#pragma unroll
+        for (int j = 1; j < N; ++j) {
+          di = e == (uint32_t)j ? d[j] : di;
+          gi = e == (uint32_t)j ? ge[j] : gi;
+        }
+        const double dd = (double)di, gg = (double)gi;
+        if (may_raise_max_rel(dd, gg, lane_top(a, l))) raise_max_rel(dd, gg, l);
+      }
+    } while (__builtin_amdgcn_ballot_w64(pend != 0) != 0);
+    fold_lanes(a, l);
+  }
+}
+
 // One whole vector per lane; idx0 = tile index of the first element of lane 0's vector.  The
 // chunks of a vector go through one copy of the code.
 template <int DT>
@@ -732,7 +833,7 @@ __device__ __forceinline__ void compare_vector(u32x4 c, u32x4 g, uint32_t idx0, 
   } else {
 #pragma unroll 1
     for (uint32_t j = 0; j < (uint32_t)CHUNKS; ++j) {
-      compare_chunk<DT, N>(c, g, idx0 + j * N, k, a);
+      compare_chunk_u8<N>(c, g, idx0 + j * N, k, a);
       drop_front<ES * N>(c);
       drop_front<ES * N>(g);
     }
@@ -865,7 +966,13 @@ __device__ __forceinline__ void compare_tile_to_partial(const TileView& tv, cons
   k.tol = tv.mode == R3_CMP_TOL;
   k.rtol = tv.rtol;
   k.atol = tv.atol;
+  __shared__ uint32_t lut[kWavesPerBlock][128];
+  k.lut = lut[wave_in_block()];
   Acc a;
+  a.tq_fix = 0;
+  a.lut_ready = 0;
+  a.lut_fix = 0;
+  a.imax = 0;
   a.wcount = 0;
   a.wfirst = 0xFFFFFFFFu;
   a.top_bits = 0;
@@ -877,7 +984,8 @@ __device__ __forceinline__ void compare_tile_to_partial(const TileView& tv, cons
   // has a checksum to add up.
   const uint64_t cks = dpp_sum(a.cks);
   uint64_t max_abs = 0;
-  if (__builtin_amdgcn_ballot_w64(dbits(a.max_abs) != 0) != 0) max_abs = dpp_max(dbits(a.max_abs));
+  const double lane_abs = (double)a.imax > a.max_abs ? (double)a.imax : a.max_abs;
+  if (__builtin_amdgcn_ballot_w64(dbits(lane_abs) != 0) != 0) max_abs = dpp_max(dbits(lane_abs));
   const uint64_t count = a.wcount;
   const uint64_t first_elem = a.wfirst != 0xFFFFFFFFu ? tv.rel_start / k.es + a.wfirst : R3_NO_INDEX;
   const uint64_t max_rel = a.top_bits;
