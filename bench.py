@@ -32,13 +32,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (profiles/*_hbm_counters.txt),
+# HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (profiles/bench_large_snapshot_and_other_workloads_hbm_counters.txt),
 # each scaled by what the same counter reads for a plain 1 GiB copy (FETCH 2.0, WRITE 1.0).
 # Valid only for the kernel source they were taken with: reported as null otherwise.
 COUNTERS = {
-    "kernels_sha256_16": "13fb7fe4b7fb8c37",
-    "jacobi": {"restore": 541102618, "validate": 269371953},
-    "large_snapshot": {"restore": 68754396689, "validate": 68734331249},
+    "kernels_sha256_16": "2f015f23b96abc61",
+    "jacobi": {"restore": 541104910, "validate": 269453416},
+    "large_snapshot": {"restore": 68754996188, "validate": 68734239300},
 }
 
 
