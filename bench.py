@@ -36,9 +36,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # each scaled by what the same counter reads for a plain 1 GiB copy (FETCH 2.0, WRITE 1.0).
 # Valid only for the kernel source they were taken with: reported as null otherwise.
 COUNTERS = {
-    "kernels_sha256_16": "2f015f23b96abc61",
-    "jacobi": {"restore": 541104910, "validate": 269453416},
-    "large_snapshot": {"restore": 68754996188, "validate": 68734239300},
+    "kernels_sha256_16": "29e68777a1f08e01",
+    "jacobi": {"restore": 541105491, "validate": 269481063},
+    "large_snapshot": {"restore": 68754989903, "validate": 68734389621},
 }
 
 

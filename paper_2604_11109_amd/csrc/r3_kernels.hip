@@ -730,7 +730,8 @@ __device__ __forceinline__ void compare_chunk(const u32x4& c, const u32x4& g, ui
 // ---- 1-byte elements: the same chunk in integer arithmetic -----------------------------
 // With C, G in 0..255 everything is exact in small integers: d = |C - G|, and both tests of
 // an element are comparisons of d with a function of G alone, read from a 256-entry table
-// that the wavefront keeps in LDS (two bytes per entry):
+// that the wavefront keeps in LDS (one 32-bit word per entry, T in the low half and Q in the
+// high half, so that each comparison reads its half of the word in place):
 //   T[G] = min(255, floor(atol + fl(rtol*G)))      mismatch under tolerance  <=>  d > T[G]
 //          (binary64, the two roundings of the rule; d is an integer, so d > thr <=> d > floor(thr);
 //          T[G] = 0 in bitwise mode, where any difference is a mismatch)
@@ -754,11 +755,10 @@ __device__ __forceinline__ void build_byte_table(const ElemKind& k, Acc& a) {
     const uint32_t T = !k.tol ? 0u : thr >= 255.0 ? 255u : (uint32_t)thr;
     const uint64_t q = ((uint64_t)a.tq_fix * (gi > 1u ? gi : 1u)) >> 16;
     const uint32_t Q = q > 255u ? 255u : (uint32_t)q;
-    entry[j] = T | (Q << 8);
+    entry[j] = T | (Q << 16);
   }
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // earlier reads of the table are done
-  k.lut[2 * lane] = entry[0] | (entry[1] << 16);
-  k.lut[2 * lane + 1] = entry[2] | (entry[3] << 16);
+  *(u32x4*)(k.lut + 4 * lane) = u32x4{entry[0], entry[1], entry[2], entry[3]};
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   __builtin_amdgcn_wave_barrier();
   a.lut_ready = 1;
@@ -771,13 +771,13 @@ __device__ __forceinline__ void compare_chunk_u8(const u32x4& c, const u32x4& g,
   constexpr uint32_t EPV = 16;
   uint32_t ge[N], d[N], tv[N];
   uint64_t m[N];
-  const uint16_t* lut = (const uint16_t*)k.lut;
+  const uint32_t* lut = k.lut;
   build_byte_table(k, a);
 #pragma unroll
   for (int e = 0; e < N; ++e) {
     const uint32_t ce = (c[e >> 2] >> (8 * (e & 3))) & 0xFFu;
     ge[e] = (g[e >> 2] >> (8 * (e & 3))) & 0xFFu;
-    d[e] = ce > ge[e] ? ce - ge[e] : ge[e] - ce;
+    d[e] = __builtin_amdgcn_sad_u8(ce, ge[e], 0u);  // |ce - ge|: the upper bytes of both are zero
     a.imax = d[e] > a.imax ? d[e] : a.imax;
   }
 #pragma unroll
@@ -785,8 +785,8 @@ __device__ __forceinline__ void compare_chunk_u8(const u32x4& c, const u32x4& g,
   uint64_t any = 0, any_rel = 0;
 #pragma unroll
   for (int e = 0; e < N; ++e) {
-    m[e] = __builtin_amdgcn_ballot_w64(d[e] > (tv[e] & 0xFFu));
-    any_rel |= __builtin_amdgcn_ballot_w64(d[e] > (tv[e] >> 8));
+    m[e] = __builtin_amdgcn_ballot_w64(d[e] > (tv[e] & 0xFFFFu));
+    any_rel |= __builtin_amdgcn_ballot_w64(d[e] > (tv[e] >> 16));
     any |= m[e];
     a.wcount += (uint32_t)__builtin_popcountll(m[e]);
   }
@@ -801,7 +801,7 @@ __device__ __forceinline__ void compare_chunk_u8(const u32x4& c, const u32x4& g,
   if (any_rel != 0) {
     uint32_t pend = 0;
 #pragma unroll
-    for (int e = 0; e < N; ++e) pend |= d[e] > (tv[e] >> 8) ? (1u << e) : 0u;
+    for (int e = 0; e < N; ++e) pend |= d[e] > (tv[e] >> 16) ? (1u << e) : 0u;
     LaneAcc l{0, 0xFFFFFFFFu, 0.0};
     do {
       if (pend != 0) {
@@ -898,8 +898,10 @@ __device__ __forceinline__ void compare_vectors(const u32x4* C, const u32x4* G, 
       }
     }
     if (__builtin_amdgcn_ballot_w64(diff != 0) != 0) {
-      // One code site for the four vectors (the kernel has to fit the instruction cache).
-#pragma unroll 1
+      // Each vector has its own copy of the chunk code (no register-indexed copies of the
+      // loaded vectors); the element-by-element careful path inside stays a rolled loop, so
+      // one element type's path is about 14 KB of the instruction cache.
+#pragma unroll
       for (uint32_t u = 0; u < (uint32_t)kUnroll; ++u) {
         const u32x4 cc = c[u], gg = g[u];
         if (__builtin_amdgcn_ballot_w64(vec_diff(cc, gg) != 0) != 0)
@@ -966,7 +968,7 @@ __device__ __forceinline__ void compare_tile_to_partial(const TileView& tv, cons
   k.tol = tv.mode == R3_CMP_TOL;
   k.rtol = tv.rtol;
   k.atol = tv.atol;
-  __shared__ uint32_t lut[kWavesPerBlock][128];
+  __shared__ uint32_t lut[kWavesPerBlock][256];
   k.lut = lut[wave_in_block()];
   Acc a;
   a.tq_fix = 0;
