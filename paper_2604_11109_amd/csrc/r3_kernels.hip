@@ -389,6 +389,8 @@ struct Acc {
   uint64_t top_bits;  // bit pattern of top = the largest relative error so far (the tile's max_rel)
   uint64_t tq_bits;   // bit pattern of tq = top cut down so that tq * |G| is exact (raise_top)
   uint32_t tq_fix;    // floor(top * 2^16), saturated: the same bound in fixed point, for 1-byte elements
+  double rtol_cut;    // a little under rtol (tolerance mode), -1 in bitwise mode; see within
+  uint32_t within;    // 1 while top <= rtol_cut: an element that cannot raise top is then no mismatch
   uint32_t lut_ready; // 1 once this wavefront has built its table of the 1-byte path
   uint32_t lut_fix;   // the tq_fix that table was built for
   uint32_t imax;      // per lane: largest integer error seen by the 1-byte path
@@ -410,7 +412,7 @@ struct ElemKind {
   bool is_float;
   bool tol;
   double rtol, atol;
-  uint32_t* lut;      // this wavefront's 512 bytes of LDS (table of the 1-byte path)
+  uint32_t* lut;      // this wavefront's 1 KiB of LDS (table of the 1-byte path)
 };
 
 // binary16 -> binary64 (exact): through the hardware conversion to binary32.
@@ -470,6 +472,7 @@ __device__ __forceinline__ void raise_top(Acc& a, double m) {
     a.tq_bits = sgpr(cut);
     const uint32_t fix = m < 0x1p15 ? (uint32_t)(m * 0x1p16) : 0x7FFFFFFFu;  // the scaling is exact
     a.tq_fix = sgpr(fix);
+    a.within = sgpr((uint32_t)(m <= a.rtol_cut));
   }
 }
 
@@ -652,7 +655,17 @@ __device__ __forceinline__ void compare_chunk(const u32x4& c, const u32x4& g, ui
   }
   // Per lane, which of its elements may raise max_rel (or are NaN / infinite).  Usually none.
   uint32_t pend = 0;
-  if (__builtin_amdgcn_ballot_w64(any_flag) != 0) {
+  const bool flagged = __builtin_amdgcn_ballot_w64(any_flag) != 0;
+  if (!flagged && a.within) {
+    // No element of the chunk can raise top, and top <= rtol_cut: every error is finite and
+    //   d <= top * |G| <= rtol * (1 - 2^-51) * |G| <= fl(rtol * |G|) <= fl(atol + fl(rtol * |G|))
+    // (the product is a normal number or the element has d == 0; adding atol >= 0 and rounding
+    // cannot go below the addend), so no element is a mismatch and the threshold is not needed.
+#pragma unroll
+    for (int e = 0; e < N; ++e) a.max_abs = max_with_abs(a.max_abs, t[e]);
+    return;
+  }
+  if (flagged) {
     bool odd = false;  // an error that is NaN or infinite: the plain predicate does not apply
 #pragma unroll
     for (int e = 0; e < N; ++e) {
@@ -972,6 +985,9 @@ __device__ __forceinline__ void compare_tile_to_partial(const TileView& tv, cons
   k.lut = lut[wave_in_block()];
   Acc a;
   a.tq_fix = 0;
+  // rtol * (1 - 2^-50), rounded: at most rtol * (1 - 2^-51).  Tiny rtol: only top == 0 counts.
+  a.rtol_cut = !k.tol ? -1.0 : k.rtol >= kTopFloor ? k.rtol - k.rtol * 0x1p-50 : 0.0;
+  a.within = k.tol ? 1u : 0u;  // top starts at 0
   a.lut_ready = 0;
   a.lut_fix = 0;
   a.imax = 0;

@@ -678,3 +678,65 @@ def test_compare_dense_differences(env, oracle, mode):
     assert_results_equal(res, exp_res, "dense differences, finite")
     assert summ.tobytes() == exp_sum.tobytes()
     assert np.isfinite(exp_res["max_rel_err"]).all()
+
+
+@pytest.mark.parametrize("atol_on", [False, True])
+def test_compare_errors_at_the_tolerance(env, oracle, atol_on):
+    """Every element differs and its relative error sits below, at and just above rtol (within a few
+    units in the last place of the threshold), so the decision turns on the two roundings of
+    atol + rtol * |G|; the first elements of each region stay well inside, the ones past the middle
+    straddle the threshold, and one region never leaves the tolerance at all."""
+    r3, ctx, torch = env
+    rng = np.random.default_rng(31337 + int(atol_on))
+    rows, parts, at = [], [], 0
+    kinds = [(ri.F64, "<f8", 2.0 ** -20), (ri.F64, "<f8", 1e-9), (ri.F32, "<f4", 1e-3), (ri.F32, "<f4", 2.0 ** -10),
+             (ri.BF16, None, 0.05), (ri.F16, "<f2", 0.01), (ri.F64, "<f8", 1e-6)]
+    for j, (dt, np_t, rtol) in enumerate(kinds):
+        es = ri.ELEM_SIZE[dt]
+        n_el = (70000 + 1000 * j) // es * 2
+        calm = j == len(kinds) - 1                          # the last region stays inside its tolerance
+        G = rng.standard_normal(n_el) * np.exp(rng.uniform(-2, 2, n_el))
+        G[G == 0] = 1.0
+        f = rng.choice([0.1, 0.5, 0.9], n_el)
+        if not calm:
+            late = np.arange(n_el) > n_el // 2
+            near = rng.choice([1.0 - 2.0 ** -40, 1.0 - 2.0 ** -52, 1.0, 1.0 + 2.0 ** -52, 1.0 + 2.0 ** -40, 1.5], n_el)
+            f = np.where(late & (rng.random(n_el) < 0.3), near, f)
+        atol = (1e-4 if dt in (ri.BF16, ri.F16) else 1e-9) if atol_on else 0.0
+        if np_t == "<f8":
+            g = G.astype("<f8")
+            # live = golden + (atol + rtol*|golden|) * f, then nudged by -1, 0, +1 pattern steps
+            c = g + np.sign(rng.standard_normal(n_el)) * (atol + rtol * np.abs(g)) * f
+            c = (c.view(np.int64) + rng.integers(-1, 2, n_el)).view("<f8")
+            gb, cb = g.view(np.uint8), np.ascontiguousarray(c).view(np.uint8)
+        elif np_t is not None:
+            g = G.astype(np_t)
+            g64 = g.astype("<f8")
+            c = (g64 + np.sign(rng.standard_normal(n_el)) * (atol + rtol * np.abs(g64)) * f).astype(np_t)
+            gb, cb = np.ascontiguousarray(g).view(np.uint8), np.ascontiguousarray(c).view(np.uint8)
+        else:
+            g = ri.f32_to_bf16_bits(G.astype("<f4"))
+            g64 = (g.astype(np.uint32) << 16).view("<f4").astype("<f8")
+            c64 = g64 + np.sign(rng.standard_normal(n_el)) * (atol + rtol * np.abs(g64)) * f
+            c = ri.f32_to_bf16_bits(c64.astype("<f4"))
+            gb, cb = np.ascontiguousarray(g).view(np.uint8), np.ascontiguousarray(c).view(np.uint8)
+        at = (at + 255) // 256 * 256
+        rows.append((at, n_el * es, dt, ri.TOL, rtol, atol))
+        parts.append((at, gb.copy(), cb.copy()))
+        at += n_el * es
+    arena = (at + 255) // 256 * 256
+    gold = rng.integers(0, 256, arena, dtype=np.uint8)
+    live = gold.copy()
+    for off, g, c in parts:
+        gold[off:off + g.size] = g
+        live[off:off + c.size] = c
+    print("case errors at the tolerance, atol", atol_on, "regions", len(rows), "bytes", arena, flush=True)
+    exp_res, exp_sum = oracle.compare(oracle.make_table(rows), live, gold)
+    res, summ = run_compare(r3, ctx, torch, rows, dev(torch, live), dev(torch, gold), arena)
+    assert_results_equal(res, exp_res, "errors at the tolerance")
+    assert summ.tobytes() == exp_sum.tobytes()
+    counts = exp_res["mismatch_count"]
+    assert (counts[:-1] > 0).all() and counts[-1] == 0       # both regimes are in the data
+    assert (exp_res["max_rel_err"] > 0).all()
+    if not atol_on:
+        assert exp_res["max_rel_err"][-1] < 1e-6             # with atol the quotient may pass rtol without a mismatch
