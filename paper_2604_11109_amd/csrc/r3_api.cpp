@@ -71,6 +71,8 @@ int lane_init(r3_ctx* ctx, r3::EvalLane& lane) {
 
 // The context's own pair of streams and ordering events, created at the first overlapped
 // submission.  Default priority, like every stream this library touches.
+void pipe_release(r3::Pipe& p);
+
 int pipe_init(r3_ctx* ctx) {
   r3::Pipe& p = ctx->pipe;
   if (p.ready) return R3_OK;
@@ -81,7 +83,10 @@ int pipe_init(r3_ctx* ctx) {
     if (e == hipSuccess) e = hipEventCreateWithFlags(&p.val_end[i], hipEventDisableTiming);
   }
   if (e == hipSuccess) e = hipEventCreateWithFlags(&p.join, hipEventDisableTiming);
-  if (e != hipSuccess) return fail_hip(ctx, e, "streams of the overlapped pipeline");
+  if (e != hipSuccess) {
+    pipe_release(p);  // nothing half-made is kept: the next submission starts over
+    return fail_hip(ctx, e, "streams of the overlapped pipeline");
+  }
   p.ready = true;
   return R3_OK;
 }
