@@ -143,3 +143,29 @@ def test_replicate_and_timing_agree_with_oracle(r3, oracle):
             exp = np.array([e["min"], e["median"], e["max"], e["mad"]], dtype=np.float32)
             assert (got == exp).all(), (n, tol, got, exp)
             assert abs(t.mean - e["mean"]) <= 1e-6 * max(1.0, abs(e["mean"]))
+
+
+def test_bench_refuses_more_than_one_gpu_and_reports_counters_only_for_the_profiled_source(monkeypatch):
+    """Host logic of the benchmark driver: a run on several GPUs is refused with a message, and
+    the measured HBM traffic is reported only while the kernel source is the profiled one."""
+    import importlib
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert p.returncode != 0
+    assert "one GPU" in (p.stdout + p.stderr)
+    sys.path.insert(0, root)
+    try:
+        bench = importlib.import_module("bench")
+    finally:
+        sys.path.pop(0)
+    monkeypatch.setitem(bench.COUNTERS, "kernels_sha256_16", "0" * 16)
+    assert bench.measured_traffic("large_snapshot", "restore") is None
+    import hashlib
+    src = os.path.join(root, "paper_2604_11109_amd", "csrc", "r3_kernels.hip")
+    monkeypatch.setitem(bench.COUNTERS, "kernels_sha256_16", hashlib.sha256(open(src, "rb").read()).hexdigest()[:16])
+    got = bench.measured_traffic("large_snapshot", "restore")
+    assert isinstance(got, int) and got >= 2 * 32 * (1 << 30)        # at least the algorithmic bytes
+    assert bench.measured_traffic("large_snapshot", "no such stage") is None
