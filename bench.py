@@ -36,9 +36,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # each scaled by what the same counter reads for a plain 1 GiB copy (FETCH 2.0, WRITE 1.0).
 # Valid only for the kernel source they were taken with: reported as null otherwise.
 COUNTERS = {
-    "kernels_sha256_16": "4beab2024c69ed6e",
-    "jacobi": {"restore": 541107592, "validate": 269493213},
-    "large_snapshot": {"restore": 68754588992, "validate": 68734431162},
+    "kernels_sha256_16": "1ee79119fcf5ac86",
+    "jacobi": {"restore": 541105126, "validate": 269493419},
+    "large_snapshot": {"restore": 68754965277, "validate": 68734378414},
 }
 
 

@@ -555,9 +555,11 @@ __device__ __forceinline__ void differing_word(uint64_t wc, uint64_t wg, uint32_
 // everywhere, so this path matters as much as the bit-equal one.  A vector is handled in
 // chunks of N elements.  The common case of a chunk needs no branch and no divide: every
 // element's error is finite and provably cannot raise max_rel; then the mismatch masks of
-// the lanes are counted on the scalar unit and max_abs is one instruction per element.  Only
-// the elements that may raise max_rel are divided, one per lane and round; a chunk in which
-// any lane sees NaN or infinity is redone element by element under the full rules.
+// the lanes are counted on the scalar unit and max_abs is one instruction per element (and
+// while the largest relative error so far is under rtol, such a chunk cannot hold a mismatch
+// either: threshold, masks and counting are skipped).  Only the elements that may raise
+// max_rel are divided, one per lane and round; a chunk in which any lane sees NaN or infinity
+// is redone element by element under the full rules.
 template <int DT> struct Elem;
 template <> struct Elem<R3_U8>   { static constexpr int size = 1; [[maybe_unused]] static constexpr bool is_float = false; };
 template <> struct Elem<R3_F32>  { static constexpr int size = 4; static constexpr bool is_float = true; };
